@@ -1,0 +1,260 @@
+"""Pins for the CPU oracle: each test ties oracle/ to a fact outside itself.
+
+The trimmed head is, by Section 2.1 and 2.3 of the paper, the full head's projection
+restricted to the draft vocabulary's rows, so the pins are: the restriction and identity
+invariants, normalisation of the softmax, brute force on tiny inputs, exact integer
+arithmetic, the FLOP count the paper prints in Table 1, closed forms, and textbook library
+routines (numpy / scipy) on the same inputs.
+"""
+import numpy as np
+import pytest
+from scipy.special import logsumexp
+
+from oracle import vt_oracle as vo
+from paper_2603_05210_amd import synth
+
+
+def _small_problem(seed=3, V=300, H=64, Vd=77, R=3, std=0.02):
+    W = synth.gen_W(seed, V, H, std)
+    h = synth.gen_h(seed, R, H)
+    ids = synth.zipf_subset(seed, V, Vd)
+    return W, h, ids
+
+
+def _read_table1(golden_dir):
+    vals = {}
+    for line in (golden_dir / "table1_flops.txt").read_text().splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        parts = line.split()
+        vals[parts[0]] = [float(x) for x in parts[1:]]
+    return vals
+
+
+# ---------------------------------------------------------------- P1 restriction invariant
+def test_trimmed_equals_full_restricted_to_subset():
+    W, h, ids = _small_problem()
+    V = W.shape[0]
+    W_sub, d2t = vo.build_subset(W, ids)
+    full = vo.draft_head(h, W, np.arange(V, dtype=np.int32), k=V)
+    trim = vo.draft_head(h, W_sub, d2t, k=len(ids))
+    # logits of the trimmed head are bit-equal to the full head's logits at the kept tokens
+    assert np.array_equal(trim.z.view(np.uint32), full.z[:, ids].view(np.uint32))
+    # log-probs are the full ones renormalised by the probability mass the subset keeps
+    # (the model-probability analogue of the coverage of Eq. 2)
+    p_full = np.exp(full.z.astype(np.float64) - logsumexp(full.z.astype(np.float64), axis=1, keepdims=True))
+    kept_mass = p_full[:, ids].sum(axis=1)
+    for r in range(h.shape[0]):
+        lp_full_at = np.log(p_full[r, ids])
+        expect = lp_full_at - np.log(kept_mass[r])
+        got = np.empty(len(ids))
+        got[trim.draft_idx[r]] = trim.logp[r]
+        assert np.max(np.abs(got - expect)) < 1e-5
+    # and the k best of the trimmed head are the full ranking with dropped tokens removed
+    keep = np.zeros(V, dtype=bool)
+    keep[ids] = True
+    for r in range(h.shape[0]):
+        full_order = full.ids[r]
+        assert np.array_equal(full_order[keep[full_order]], trim.ids[r])
+
+
+# ---------------------------------------------------------------- P2 identity subset
+def test_identity_subset_reproduces_untrimmed_head():
+    W, h, _ = _small_problem(seed=5)
+    V = W.shape[0]
+    ident = np.arange(V, dtype=np.int32)
+    W_sub, d2t = vo.build_subset(W, ident)
+    assert np.array_equal(W_sub, W)
+    assert np.array_equal(d2t, ident)
+    a = vo.draft_head(h, W_sub, d2t, k=7)
+    # untrimmed head written with numpy on the widened inputs
+    zf = synth.bf16_to_f32(h).astype(np.float64) @ synth.bf16_to_f32(W).astype(np.float64).T
+    assert np.array_equal(a.ids, np.argsort(-zf, axis=1, kind="stable")[:, :7])
+
+
+def test_gather_is_bit_exact_and_order_preserving():
+    W, _, _ = _small_problem(seed=8)
+    ids = np.array([250, 3, 17, 299, 0, 42], dtype=np.int32)  # unsorted on purpose
+    W_sub, d2t = vo.build_subset(W, ids)
+    assert np.array_equal(d2t, ids)
+    for j, t in enumerate(ids):
+        assert np.array_equal(W_sub[j], W[t])
+
+
+def test_subset_validation():
+    W, _, _ = _small_problem()
+    with pytest.raises(ValueError):
+        vo.build_subset(W, np.array([1, 2, 300], dtype=np.int32))
+    with pytest.raises(ValueError):
+        vo.build_subset(W, np.array([1, -1], dtype=np.int32))
+    with pytest.raises(ValueError):
+        vo.build_subset(W, np.array([1, 2, 1], dtype=np.int32))
+    W_sub, d2t = vo.build_subset(W, np.array([4, 9], dtype=np.int32))
+    h = synth.gen_h(0, 1, W.shape[1])
+    with pytest.raises(ValueError):
+        vo.draft_head(h, W_sub, d2t, k=3)
+    with pytest.raises(ValueError):
+        vo.draft_head(h, W_sub, d2t, k=0)
+
+
+# ---------------------------------------------------------------- P3 normalisation
+@pytest.mark.parametrize("scale", [1.0, 10.0, 40.0])
+def test_log_softmax_normalises_to_one(scale):
+    W, h, ids = _small_problem(seed=11, V=500, H=128, Vd=200, R=4, std=0.05)
+    hf = synth.bf16_to_f32(h) * np.float32(scale)
+    h = synth.f32_to_bf16(hf).reshape(h.shape)
+    W_sub, d2t = vo.build_subset(W, ids)
+    res = vo.draft_head(h, W_sub, d2t, k=len(ids))
+    total = np.exp(res.logp.astype(np.float64)).sum(axis=1)
+    assert np.max(np.abs(total - 1.0)) < 1e-5
+    # best-first ordering
+    assert np.all(np.diff(res.logp, axis=1) <= 0)
+
+
+def test_lse_matches_library_logsumexp():
+    rng = np.random.default_rng(0)
+    for n, spread in [(1, 1.0), (7, 1.0), (1000, 5.0), (4096, 60.0)]:
+        z = (rng.standard_normal(n) * spread).astype(np.float32)
+        assert abs(vo.lse_row(z) - logsumexp(z.astype(np.float64))) < 2e-6 * max(1.0, abs(float(z.max())))
+
+
+# ---------------------------------------------------------------- P4 brute-force top-k
+def _brute_topk(z, k):
+    z = [float(x) for x in z]
+    taken = []
+    for _ in range(k):
+        best = None
+        for j, v in enumerate(z):
+            if j in taken:
+                continue
+            if best is None or v > z[best]:  # strict: the lowest index wins a tie
+                best = j
+        taken.append(best)
+    return taken
+
+
+def test_topk_matches_brute_force_with_ties():
+    rng = np.random.default_rng(1)
+    for n in (1, 2, 5, 17, 64):
+        for trial in range(4):
+            z = rng.integers(-3, 4, size=n).astype(np.float32)  # many exact ties
+            if trial == 3:
+                z = rng.standard_normal(n).astype(np.float32)
+            for k in range(1, n + 1):
+                assert list(vo.topk_row(z, k)) == _brute_topk(z, k)
+
+
+def test_duplicate_rows_tie_goes_to_lower_draft_index():
+    H = 32
+    W = synth.gen_W(2, 40, H, 0.5)
+    W[7] = W[31]
+    W[12] = W[31]
+    h = synth.gen_h(2, 2, H)
+    # unsorted ids: position in the list, not the token id, decides a tie
+    ids = np.array([31, 5, 12, 7, 20], dtype=np.int32)
+    W_sub, d2t = vo.build_subset(W, ids)
+    res = vo.draft_head(h, W_sub, d2t, k=5)
+    for r in range(2):
+        assert list(res.draft_idx[r]) == _brute_topk(res.z[r], 5)
+        pos = {int(t): p for p, t in enumerate(res.ids[r])}
+        assert pos[31] < pos[12] < pos[7]          # draft indices 0 < 2 < 3
+        assert pos[12] == pos[31] + 1 and pos[7] == pos[12] + 1
+        assert np.array_equal(res.ids[r], ids[res.draft_idx[r]])
+
+
+# ---------------------------------------------------------------- P5 cost closed form
+def test_flop_count_is_2dk_per_row(golden_dir):
+    W, h, ids = _small_problem(seed=4, V=200, H=96, Vd=50, R=3)
+    W_sub, _ = vo.build_subset(W, ids)
+    _, flops = vo.logits(h, W_sub, return_flops=True)
+    assert flops == 3 * 2 * 96 * 50
+    # Table 1's LM-head row: d = 4096, V = 128256 -> 1050.7 M
+    t = _read_table1(golden_dir)
+    d, V = int(t["d"][0]), int(t["V"][0])
+    Wz = np.zeros((V, d), dtype=np.uint16)
+    hz = np.zeros((1, d), dtype=np.uint16)
+    _, flops = vo.logits(hz, Wz, return_flops=True)
+    assert flops == 2 * d * V == 1050673152
+    assert round(flops / 1e6, 1) == t["lm_head"][0]
+    fixed = sum(t[c][0] for c in ("feature_fusion", "attention", "feed_forward"))
+    assert abs(100.0 * (flops / 1e6) / (fixed + flops / 1e6) - t["lm_head"][1]) < 0.06
+    assert Wz.nbytes == flops  # bytes of bf16 W_sub streamed per step equal the FLOP count
+
+
+# ---------------------------------------------------------------- P6 zero hidden state
+def test_zero_hidden_state_gives_uniform_distribution():
+    W, _, ids = _small_problem(seed=6, V=400, H=64, Vd=123)
+    W_sub, d2t = vo.build_subset(W, ids)
+    h = np.zeros((2, 64), dtype=np.uint16)
+    res = vo.draft_head(h, W_sub, d2t, k=9)
+    assert np.all(res.z == 0.0)
+    assert np.allclose(res.logp, -np.log(123.0), atol=1e-6)
+    assert np.array_equal(res.ids, np.tile(d2t[:9], (2, 1)))
+
+
+# ---------------------------------------------------------------- P7 one-hot hidden state
+def test_one_hot_hidden_state_reads_a_column():
+    W, _, ids = _small_problem(seed=7, V=300, H=64, Vd=80)
+    W_sub, d2t = vo.build_subset(W, ids)
+    h = np.zeros((3, 64), dtype=np.uint16)
+    cols, scales = [0, 17, 63], [1.0, -2.5, 0.375]
+    for r, (i, c) in enumerate(zip(cols, scales)):
+        h[r, i] = synth.f32_to_bf16(np.array([c], dtype=np.float32))[0]
+    res = vo.draft_head(h, W_sub, d2t, k=4)
+    Wf = synth.bf16_to_f32(W_sub)
+    for r, (i, c) in enumerate(zip(cols, scales)):
+        assert np.array_equal(res.z[r], np.float32(c) * Wf[:, i])
+
+
+# ---------------------------------------------------------------- P8 exact integer arithmetic
+def test_small_integer_inputs_match_int64_matmul_exactly():
+    H, Vd, R = 256, 150, 5
+    Wb = synth.small_int_bf16(9, 0, (Vd, H))
+    hb = synth.small_int_bf16(9, 1, (R, H))
+    exact = synth.bf16_to_f32(hb).astype(np.int64) @ synth.bf16_to_f32(Wb).astype(np.int64).T
+    res = vo.draft_head(hb, Wb, np.arange(Vd, dtype=np.int32), k=12)
+    assert np.array_equal(res.z.astype(np.int64), exact)
+    assert np.array_equal(res.z, exact.astype(np.float32))
+    # the order is then fixed by integers: (value descending, index ascending)
+    for r in range(R):
+        order = sorted(range(Vd), key=lambda j: (-int(exact[r, j]), j))[:12]
+        assert list(res.draft_idx[r]) == order
+
+
+# ---------------------------------------------------------------- P9 library cross-check
+@pytest.mark.parametrize("shape", [(3, 64, 77), (2, 512, 1000), (1, 2048, 300)])
+def test_against_numpy_float64_reference(shape):
+    R, H, Vd = shape
+    W = synth.gen_W(21, 3 * Vd, H)
+    h = synth.gen_h(21, R, H)
+    ids = synth.zipf_subset(21, 3 * Vd, Vd)
+    W_sub, d2t = vo.build_subset(W, ids)
+    k = min(10, Vd)
+    res = vo.draft_head(h, W_sub, d2t, k=k)
+    z64 = synth.bf16_to_f32(h).astype(np.float64) @ synth.bf16_to_f32(W[ids]).astype(np.float64).T
+    assert np.max(np.abs(res.z - z64)) < 1e-4
+    assert np.max(np.abs(vo.logits_f64(h, W_sub) - z64)) < 1e-10
+    logp64 = z64 - logsumexp(z64, axis=1, keepdims=True)
+    for r in range(R):
+        ref_order = np.argsort(-z64[r], kind="stable")[:k]
+        got = res.draft_idx[r]
+        for p in range(k):
+            if got[p] != ref_order[p]:  # only a near-tie may reorder
+                assert abs(z64[r, got[p]] - z64[r, ref_order[p]]) < 1e-4
+        assert np.max(np.abs(res.logp[r] - logp64[r, got])) < 1e-4
+        assert np.array_equal(res.ids[r], ids[got])
+        assert abs(res.lse[r] - logsumexp(z64[r])) < 1e-4
+
+
+def test_transposed_or_sign_flipped_reference_would_be_caught():
+    """The library cross-check has teeth: plausible mistakes move logits far beyond its bound."""
+    R, H, Vd = 2, 64, 64
+    W = synth.gen_W(30, Vd, H, 0.5)
+    h = synth.gen_h(30, R, H)
+    z = vo.logits(h, W)
+    Wf, hf = synth.bf16_to_f32(W).astype(np.float64), synth.bf16_to_f32(h).astype(np.float64)
+    good = hf @ Wf.T
+    assert np.max(np.abs(z - good)) < 1e-4
+    assert np.max(np.abs(z - (-good))) > 1.0                      # wrong sign
+    assert np.max(np.abs(z - (hf @ Wf)[:, :Vd])) > 1.0            # transposed operand (square W)
+    assert np.max(np.abs(z - (hf[:, :-1] @ Wf[:, :-1].T))) > 1e-3  # dropped term
