@@ -1,0 +1,140 @@
+/*
+ * vt.h -- C ABI of the trimmed-vocabulary draft LM head for AMD MI355X (gfx950).
+ *
+ * The paper (Section 2.1) replaces the draft model's vocabulary V (|V| = V tokens) by a
+ * subset V_d of k = |V_d| tokens; only the language-modelling head depends on that size
+ * (Section 2.3: a linear projection from hidden size d to k logits, 2*d*k FLOPs per row).
+ * This library is that head:
+ *
+ *   vt_build_subset   once per draft vocabulary: gathers the rows of the full unembedding
+ *                     matrix that belong to V_d into a compact W_sub[V_draft,H] and writes
+ *                     the draft-to-target index buffer d2t (Section 1, EAGLE-3's buffers).
+ *   vt_draft_head     once per draft step: logits = h . W_sub^T, softmax statistics over V_d,
+ *                     the k best draft tokens per row, mapped through d2t to ids in V, with
+ *                     their log-probabilities.
+ *
+ * Conventions
+ *   - Every pointer documented "device" is a HIP device pointer on the current device;
+ *     "host" pointers are ordinary memory.  The library never frees or keeps a caller's
+ *     pointer.  Inputs are never modified; outputs are fully overwritten on success.
+ *   - bf16 values travel as uint16_t bit patterns.  Matrices are row-major and contiguous.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Errors are return codes only.  Argument errors are detected on the host before any
+ *     launch: on a non-VT_OK return nothing was launched and no output was touched
+ *     (exception: VT_ERR_DEVICE may be returned after a partial launch sequence).
+ *   - Preconditions: H % 8 == 0 (rows are moved in 128-bit pieces), 1 <= k <= min(V_draft,
+ *     VT_MAX_K), rows >= 1, all sizes below 2^31, device pointers 16-byte aligned.
+ *   - Non-finite inputs give undefined results.
+ */
+#ifndef VT_H_
+#define VT_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VT_MAX_K 64
+
+typedef enum {
+    VT_OK = 0,
+    VT_ERR_NULL = 1,      /* a required pointer is NULL                                  */
+    VT_ERR_SHAPE = 2,     /* rows, H, V or V_draft out of range, or H % 8 != 0            */
+    VT_ERR_K = 3,         /* k < 1, k > V_draft or k > VT_MAX_K                           */
+    VT_ERR_ID_RANGE = 4,  /* a token id is outside [0, V)                                 */
+    VT_ERR_ID_DUP = 5,    /* a token id occurs twice (V_d is a set)                       */
+    VT_ERR_WORKSPACE = 6, /* workspace missing or smaller than the size query's answer    */
+    VT_ERR_ALIGN = 7,     /* a device pointer is not 16-byte aligned                      */
+    VT_ERR_DEVICE = 8     /* the HIP runtime reported an error                            */
+} vt_status;
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int vt_version(void);
+
+/* Static, human-readable name of a status code. */
+const char *vt_status_str(vt_status s);
+
+/*
+ * Section 2.1 / Section 1 (d2t buffer).  W_sub_out[j,:] = full_W[token_ids[j],:] bit for bit,
+ * d2t_out[j] = token_ids[j], for j in [0, V_draft).  The order of token_ids defines the draft
+ * indices (pass them ascending to make "lower draft index" mean "lower target id").
+ *
+ *   full_W     device, [V,H] bf16          token_ids  device, [V_draft] int32
+ *   W_sub_out  device, [V_draft,H] bf16    d2t_out    device, [V_draft] int32
+ *
+ * The ids are checked on the device first (range and distinctness); the call waits for that
+ * check, so VT_ERR_ID_RANGE / VT_ERR_ID_DUP are returned with the outputs untouched.  The
+ * gather itself is then enqueued on `stream` and the call returns without waiting for it.
+ * Allocates and frees a V-bit scratch bitmap internally (this is a set-up call, not a
+ * per-step call).
+ */
+vt_status vt_build_subset(const uint16_t *full_W, int64_t V, int64_t H, const int32_t *token_ids,
+                          int64_t V_draft, uint16_t *W_sub_out, int32_t *d2t_out, void *stream);
+
+/* Host-side check of a host copy of the id list: VT_OK, VT_ERR_NULL, VT_ERR_SHAPE,
+ * VT_ERR_ID_RANGE or VT_ERR_ID_DUP.  Touches no device. */
+vt_status vt_check_token_ids_host(const int32_t *token_ids_host, int64_t V_draft, int64_t V);
+
+/* Pure host argument checks, exactly the ones the two entry points run before launching. */
+vt_status vt_validate_build_subset_args(const void *full_W, int64_t V, int64_t H, const void *token_ids,
+                                        int64_t V_draft, const void *W_sub_out, const void *d2t_out);
+vt_status vt_validate_draft_head_args(const void *h, int64_t rows, int64_t H, const void *W_sub,
+                                      const void *d2t, int64_t V_draft, int k, const void *out_target_ids,
+                                      const void *out_logprobs, const void *workspace, size_t workspace_bytes);
+
+/* Bytes of device workspace vt_draft_head needs for this shape (0 on invalid arguments).
+ * A pure function of its arguments: it does not depend on the device. */
+size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k);
+
+/* Which kernel family serves this shape: 0 = streaming row-split dot product (memory bound,
+ * rows <= 16), 1 = bf16 MFMA thin GEMM (rows > 16); -1 on invalid arguments. */
+int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
+
+/*
+ * One draft step (Section 2.3's head over V_d, then the candidate proposal of Section 1):
+ *   z[r,j]   = sum_i h[r,i] * W_sub[j,i]             bf16 inputs, fp32 accumulation
+ *   lse[r]   = log sum_j exp(z[r,j])                  over the V_draft draft tokens only
+ *   the k largest z[r,.] per row, best first, equal logits ordered by lower draft index j
+ *   out_target_ids[r,p] = d2t[j_p],  out_logprobs[r,p] = z[r,j_p] - lse[r]
+ *
+ *   h               device, [rows,H] bf16        W_sub  device, [V_draft,H] bf16
+ *   d2t             device, [V_draft] int32
+ *   out_target_ids  device, [rows,k] int32       out_logprobs  device, [rows,k] fp32
+ *   workspace       device, >= vt_draft_head_workspace_bytes(...) bytes, 16-byte aligned,
+ *                   contents need not be initialised and are clobbered
+ *
+ * Asynchronous on `stream`: no allocation, no synchronisation, no host read.  Concurrent
+ * calls must not share a workspace.  The logits are never written to memory.
+ */
+vt_status vt_draft_head(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
+                        const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
+                        float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Test hook, same computation through the same kernels, which additionally store
+ *   logits_out  device, [rows,V_draft] fp32 (may be NULL)
+ *   lse_out     device, [rows] fp32         (may be NULL)
+ */
+vt_status vt_draft_head_debug(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
+                              const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
+                              float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream,
+                              float *logits_out, float *lse_out);
+
+/*
+ * Timing of the dominant kernel, for roofline reporting.  When enabled, every later
+ * vt_draft_head call records a HIP event pair around its projection kernel (the streaming
+ * dot product or the MFMA GEMM, not the small merge kernel) on the call's own stream.
+ * vt_kernel_timing_read waits for the recorded events, returns the number of timed launches
+ * and their total duration in milliseconds, and resets the counters.  Off by default; at most
+ * VT_TIMING_MAX_EVENTS launches are kept between reads.
+ */
+#define VT_TIMING_MAX_EVENTS 4096
+vt_status vt_kernel_timing_enable(int on);
+vt_status vt_kernel_timing_read(int *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VT_H_ */

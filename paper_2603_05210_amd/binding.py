@@ -1,0 +1,205 @@
+"""Thin Python binding of the C ABI in include/vt.h: argument marshalling only.
+
+Tensors are torch tensors used purely as device memory (bf16 data may be torch.bfloat16 or a
+16-bit integer view of the same bits); the current torch stream is passed as the HIP stream.
+Every step of the head runs inside libvt.so.  There is no fallback: if the library is missing
+or cannot be loaded, importing callers get an error.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_PKG = Path(__file__).resolve().parent
+LIB_PATH = _PKG / "libvt.so"
+
+VT_OK = 0
+VT_MAX_K = 64
+STATUS_NAMES = {
+    0: "VT_OK", 1: "VT_ERR_NULL", 2: "VT_ERR_SHAPE", 3: "VT_ERR_K", 4: "VT_ERR_ID_RANGE",
+    5: "VT_ERR_ID_DUP", 6: "VT_ERR_WORKSPACE", 7: "VT_ERR_ALIGN", 8: "VT_ERR_DEVICE",
+}
+
+# every symbol include/vt.h declares
+EXPORTS = (
+    "vt_version", "vt_status_str", "vt_build_subset", "vt_check_token_ids_host",
+    "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
+    "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug", "vt_kernel_timing_enable",
+    "vt_kernel_timing_read",
+)
+
+
+class VtError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s" % (where, status_str(status)))
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise RuntimeError("%s is missing: build it with `python -m paper_2603_05210_amd.build` "
+                               "(or __graft_entry__.build())" % LIB_PATH)
+        L = ctypes.CDLL(str(LIB_PATH))
+        p, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+        L.vt_version.restype = i32
+        L.vt_status_str.restype = ctypes.c_char_p
+        L.vt_status_str.argtypes = [i32]
+        L.vt_build_subset.restype = i32
+        L.vt_build_subset.argtypes = [p, i64, i64, p, i64, p, p, p]
+        L.vt_check_token_ids_host.restype = i32
+        L.vt_check_token_ids_host.argtypes = [p, i64, i64]
+        L.vt_validate_build_subset_args.restype = i32
+        L.vt_validate_build_subset_args.argtypes = [p, i64, i64, p, i64, p, p]
+        L.vt_validate_draft_head_args.restype = i32
+        L.vt_validate_draft_head_args.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz]
+        L.vt_draft_head_workspace_bytes.restype = sz
+        L.vt_draft_head_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.vt_draft_head_regime.restype = i32
+        L.vt_draft_head_regime.argtypes = [i64, i64, i64, i32]
+        L.vt_draft_head.restype = i32
+        L.vt_draft_head.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p]
+        L.vt_draft_head_debug.restype = i32
+        L.vt_draft_head_debug.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p]
+        L.vt_kernel_timing_enable.restype = i32
+        L.vt_kernel_timing_enable.argtypes = [i32]
+        L.vt_kernel_timing_read.restype = i32
+        L.vt_kernel_timing_read.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+        _lib = L
+    return _lib
+
+
+def status_str(status: int) -> str:
+    return lib().vt_status_str(int(status)).decode()
+
+
+def _stream_ptr(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _dev16(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda or not t.is_contiguous() or t.element_size() != 2:
+        raise TypeError("%s must be a contiguous 16-bit device tensor (bf16 bits)" % name)
+    return t
+
+
+def _devi32(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda or not t.is_contiguous() or t.dtype != torch.int32:
+        raise TypeError("%s must be a contiguous int32 device tensor" % name)
+    return t
+
+
+def vt_version() -> int:
+    return int(lib().vt_version())
+
+
+def vt_draft_head_workspace_bytes(rows: int, H: int, V_draft: int, k: int) -> int:
+    return int(lib().vt_draft_head_workspace_bytes(rows, H, V_draft, k))
+
+
+def vt_draft_head_regime(rows: int, H: int, V_draft: int, k: int) -> int:
+    return int(lib().vt_draft_head_regime(rows, H, V_draft, k))
+
+
+def vt_check_token_ids_host(ids_host, V: int) -> int:
+    """Status code for a host array of ids against vocabulary size V (touches no device)."""
+    import numpy as np
+    a = np.ascontiguousarray(ids_host, dtype=np.int32)
+    return int(lib().vt_check_token_ids_host(a.ctypes.data_as(ctypes.c_void_p), a.shape[0], V))
+
+
+def vt_build_subset(full_W: torch.Tensor, token_ids: torch.Tensor, W_sub_out: torch.Tensor | None = None,
+                    d2t_out: torch.Tensor | None = None):
+    """W_sub[V_draft,H], d2t[V_draft] for the draft vocabulary `token_ids` (device int32)."""
+    _dev16(full_W, "full_W")
+    _devi32(token_ids, "token_ids")
+    V, H = full_W.shape
+    Vd = token_ids.shape[0]
+    if W_sub_out is None:
+        W_sub_out = torch.empty((Vd, H), dtype=full_W.dtype, device=full_W.device)
+    if d2t_out is None:
+        d2t_out = torch.empty((Vd,), dtype=torch.int32, device=full_W.device)
+    _dev16(W_sub_out, "W_sub_out")
+    _devi32(d2t_out, "d2t_out")
+    with torch.cuda.device(full_W.device):
+        st = lib().vt_build_subset(full_W.data_ptr(), V, H, token_ids.data_ptr(), Vd, W_sub_out.data_ptr(),
+                                   d2t_out.data_ptr(), _stream_ptr(full_W))
+    if st != VT_OK:
+        raise VtError(st, "vt_build_subset")
+    return W_sub_out, d2t_out
+
+
+class Workspace:
+    """A reusable device buffer sized by vt_draft_head_workspace_bytes."""
+
+    def __init__(self, device):
+        self.device = device
+        self.buf = torch.empty(0, dtype=torch.uint8, device=device)
+
+    def get(self, nbytes: int) -> torch.Tensor:
+        if self.buf.numel() < nbytes:
+            self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        return self.buf
+
+
+def vt_draft_head(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor, k: int,
+                  out_target_ids: torch.Tensor | None = None, out_logprobs: torch.Tensor | None = None,
+                  workspace: torch.Tensor | None = None, logits_out: torch.Tensor | None = None,
+                  lse_out: torch.Tensor | None = None):
+    """One draft step: (target ids [rows,k] int32 best first, log-probs [rows,k] fp32).
+
+    Passing logits_out / lse_out routes through vt_draft_head_debug (test hook).
+    """
+    _dev16(h, "h")
+    _dev16(W_sub, "W_sub")
+    _devi32(d2t, "d2t")
+    rows, H = h.shape
+    Vd, H2 = W_sub.shape
+    if H2 != H or d2t.shape[0] != Vd:
+        raise ValueError("shape mismatch between h, W_sub and d2t")
+    dev = h.device
+    if out_target_ids is None:
+        out_target_ids = torch.empty((rows, k), dtype=torch.int32, device=dev)
+    if out_logprobs is None:
+        out_logprobs = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    need = vt_draft_head_workspace_bytes(rows, H, Vd, k)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    L = lib()
+    with torch.cuda.device(dev):
+        if logits_out is None and lse_out is None:
+            st = L.vt_draft_head(h.data_ptr(), rows, H, W_sub.data_ptr(), d2t.data_ptr(), Vd, k,
+                                 out_target_ids.data_ptr(), out_logprobs.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel(), _stream_ptr(h))
+        else:
+            st = L.vt_draft_head_debug(h.data_ptr(), rows, H, W_sub.data_ptr(), d2t.data_ptr(), Vd, k,
+                                       out_target_ids.data_ptr(), out_logprobs.data_ptr(), workspace.data_ptr(),
+                                       workspace.numel(), _stream_ptr(h),
+                                       None if logits_out is None else logits_out.data_ptr(),
+                                       None if lse_out is None else lse_out.data_ptr())
+    if st != VT_OK:
+        raise VtError(st, "vt_draft_head")
+    return out_target_ids, out_logprobs
+
+
+def vt_kernel_timing_enable(on: bool) -> None:
+    st = lib().vt_kernel_timing_enable(1 if on else 0)
+    if st != VT_OK:
+        raise VtError(st, "vt_kernel_timing_enable")
+
+
+def vt_kernel_timing_read():
+    """(launches, total milliseconds) of the projection kernel since the last read."""
+    n = ctypes.c_int(0)
+    ms = ctypes.c_double(0.0)
+    st = lib().vt_kernel_timing_read(ctypes.byref(n), ctypes.byref(ms))
+    if st != VT_OK:
+        raise VtError(st, "vt_kernel_timing_read")
+    return int(n.value), float(ms.value)

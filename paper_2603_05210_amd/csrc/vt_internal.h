@@ -1,0 +1,62 @@
+// Host-side plan of one vt_draft_head call and the launchers of the kernel families.
+// Everything here is internal to the library (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace vt {
+
+// Streaming regime (rows <= kGemvMaxRows): workgroups of kGemvThreads threads, each wave
+// streams groups of J consecutive W_sub rows.
+constexpr int kGemvMaxRows = 16;
+constexpr int kGemvThreads = 512;
+constexpr int kGemvWaves = kGemvThreads / 64;
+constexpr int kGemvMaxBlocks = 512;
+constexpr int kMergeThreads = 256;
+
+struct Plan {
+    int regime;  // 0 streaming dot product, 1 MFMA GEMM
+    int rows, H, Vd, k;
+    int KP;      // list length carried in the kernels: k rounded up to a power of two
+    // streaming regime
+    int NR;      // rows rounded up to a power of two
+    int J;       // W_sub rows a wave reduces together
+    // GEMM regime
+    int tile;    // index into the table of tile shapes
+    int n_vtiles, n_rtiles;
+    // both
+    int blocks;  // workgroups of the projection kernel
+    int P;       // partial results per row handed to the merge kernel
+    size_t off_val, off_idx, off_stat, total_bytes;
+};
+
+// Fills `p`; returns false when the shape is not servable (caller has validated ranges).
+bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p);
+
+struct HeadArgs {
+    const uint16_t* h;
+    const uint16_t* W;
+    const int32_t* d2t;
+    int32_t* out_ids;
+    float* out_logp;
+    float* part_val;   // [rows][P][KP]
+    int32_t* part_idx; // [rows][P][KP]
+    float2* part_stat; // [rows][P]  (max, sum exp(z - max))
+    float* logits_out; // optional [rows][Vd]
+    float* lse_out;    // optional [rows]
+};
+
+hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s);
+hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s);
+hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s);
+hipError_t launch_check_ids(const int32_t* ids, int Vd, int V, uint32_t* bitmap, int* err, hipStream_t s);
+hipError_t launch_gather(const uint16_t* W, int H, const int32_t* ids, int Vd, uint16_t* W_sub, int32_t* d2t,
+                         hipStream_t s);
+
+// GEMM tile shapes (vocab x rows per workgroup) and their partial counts; defined with the kernel.
+int gemm_pick_tile(int rows, int Vd, int KP);
+void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile);
+
+}  // namespace vt

@@ -1,0 +1,171 @@
+// Final stage of a draft step and the one-time subset construction.
+//
+// merge_kernel: per hidden-state row, combines the P partial results (softmax statistics and
+// sorted candidate lists) that the projection kernel left in the workspace into the row's
+// log-sum-exp over V_d and its k best draft tokens, then maps them through the
+// draft-to-target buffer (Section 1 of the paper: EAGLE-3 style d2t) and emits
+// log-probabilities.  The merge uses the strict (logit, index) order, so its result does not
+// depend on how the vocabulary was split.
+//
+// check_ids / gather kernels: Section 2.1's V_d as a list of token ids -> W_sub and d2t.
+#include "vt_device.h"
+#include "vt_internal.h"
+
+namespace vt {
+
+template <int KP>
+__global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __restrict__ part_val,
+                                                              const int32_t* __restrict__ part_idx,
+                                                              const float2* __restrict__ part_stat, int P, int k,
+                                                              const int32_t* __restrict__ d2t,
+                                                              int32_t* __restrict__ out_ids,
+                                                              float* __restrict__ out_logp,
+                                                              float* __restrict__ lse_out)
+{
+    constexpr int NW = kMergeThreads / kWave;
+    __shared__ float sm_val[NW][KP];
+    __shared__ int sm_idx[NW][KP];
+    __shared__ float2 sm_stat[NW];
+
+    const int r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+
+    TopList<KP> L;
+    L.clear();
+    float m = neg_inf(), s = 0.0f;
+    for (int p = tid; p < P; p += kMergeThreads) {
+        const size_t slot = (size_t)r * P + p;
+        const float2 st = part_stat[slot];
+        stat_merge(m, s, st.x, st.y);
+        const float* pv = part_val + slot * KP;
+        const int32_t* pi = part_idx + slot * KP;
+#pragma unroll 1
+        for (int q = 0; q < KP; ++q) {  // partial lists are sorted: stop at the first loser
+            const float x = pv[q];
+            const int ix = pi[q];
+            if (!better(x, ix, L.v[KP - 1], L.i[KP - 1]))
+                break;
+            L.insert(x, ix);
+        }
+    }
+
+    wave_stat_merge(m, s, true);
+    float ov;
+    int oi;
+    wave_merge<KP>(L, true, lane, ov, oi);
+    if (lane < KP) {
+        sm_val[wave][lane] = ov;
+        sm_idx[wave][lane] = oi;
+    }
+    if (lane == 0)
+        sm_stat[wave] = make_float2(m, s);
+    __syncthreads();
+
+    if (wave == 0) {
+        const bool act = lane < NW;
+        TopList<KP> T;
+        T.clear();
+        float mv = neg_inf(), sv = 0.0f;
+        if (act) {
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                T.v[q] = sm_val[lane][q];
+                T.i[q] = sm_idx[lane][q];
+            }
+            mv = sm_stat[lane].x;
+            sv = sm_stat[lane].y;
+        }
+        wave_stat_merge(mv, sv, act);
+        wave_merge<KP>(T, act, lane, ov, oi);
+        const float lse = mv + __logf(sv);
+        if (lane < k) {
+            out_ids[(size_t)r * k + lane] = (oi != kIdxNone) ? d2t[oi] : -1;
+            out_logp[(size_t)r * k + lane] = ov - lse;
+        }
+        if (lane == 0 && lse_out != nullptr)
+            lse_out[r] = lse;
+    }
+}
+
+hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s)
+{
+#define VT_MERGE_CASE(KPV)                                                                                   \
+    case KPV:                                                                                                \
+        hipLaunchKernelGGL(merge_kernel<KPV>, dim3(p.rows), dim3(kMergeThreads), 0, s, a.part_val, a.part_idx, \
+                           a.part_stat, p.P, p.k, a.d2t, a.out_ids, a.out_logp, a.lse_out);                  \
+        break;
+    switch (p.KP) {
+        VT_MERGE_CASE(1)
+        VT_MERGE_CASE(2)
+        VT_MERGE_CASE(4)
+        VT_MERGE_CASE(8)
+        VT_MERGE_CASE(16)
+        VT_MERGE_CASE(32)
+        VT_MERGE_CASE(64)
+    default:
+        return hipErrorInvalidValue;
+    }
+#undef VT_MERGE_CASE
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ subset construction
+
+// err bit 0: an id outside [0,V); bit 1: an id seen twice.  bitmap has ceil(V/32) zeroed words.
+__global__ void check_ids_kernel(const int32_t* __restrict__ ids, int Vd, int V, uint32_t* bitmap, int* err)
+{
+    for (int j = blockIdx.x * blockDim.x + threadIdx.x; j < Vd; j += gridDim.x * blockDim.x) {
+        const int id = ids[j];
+        if (id < 0 || id >= V) {
+            atomicOr(err, 1);
+        } else {
+            const uint32_t bit = 1u << (id & 31);
+            const uint32_t old = atomicOr(&bitmap[id >> 5], bit);
+            if (old & bit)
+                atomicOr(err, 2);
+        }
+    }
+}
+
+// One wave per W_sub row: 128-bit copies of the source row, 1 KiB per wave instruction.
+__global__ void __launch_bounds__(256) gather_kernel(const u32x4* __restrict__ W, int nchunk,
+                                                     const int32_t* __restrict__ ids, int Vd,
+                                                     u32x4* __restrict__ W_sub, int32_t* __restrict__ d2t)
+{
+    const int lane = threadIdx.x & 63;
+    const int gw = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+    const int nw = gridDim.x * (blockDim.x >> 6);
+    for (int j = gw; j < Vd; j += nw) {
+        const int id = ids[j];
+        const u32x4* src = W + (size_t)id * nchunk;
+        u32x4* dst = W_sub + (size_t)j * nchunk;
+        for (int c = lane; c < nchunk; c += kWave)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(src + c), dst + c);
+        if (lane == 0)
+            d2t[j] = id;
+    }
+}
+
+hipError_t launch_check_ids(const int32_t* ids, int Vd, int V, uint32_t* bitmap, int* err, hipStream_t s)
+{
+    int blocks = (Vd + 255) / 256;
+    if (blocks > 1024)
+        blocks = 1024;
+    hipLaunchKernelGGL(check_ids_kernel, dim3(blocks), dim3(256), 0, s, ids, Vd, V, bitmap, err);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather(const uint16_t* W, int H, const int32_t* ids, int Vd, uint16_t* W_sub, int32_t* d2t,
+                         hipStream_t s)
+{
+    int blocks = (Vd + 3) / 4;
+    if (blocks > 8192)
+        blocks = 8192;
+    hipLaunchKernelGGL(gather_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const u32x4*>(W), H / 8, ids,
+                       Vd, reinterpret_cast<u32x4*>(W_sub), d2t);
+    return hipGetLastError();
+}
+
+}  // namespace vt

@@ -1,0 +1,258 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle on the same seeded inputs.
+
+Small cases are compared in full (every logit, every id, every log-prob) at sizes that span
+several tiles / waves / workgroups with ragged tails; the five full-size workloads are compared
+in full where the oracle finishes in seconds and on sampled rows otherwise.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2603_05210_amd as vt
+from oracle import vt_oracle as vo
+from paper_2603_05210_amd import synth
+from tests.parity_util import check_head, dev_bits, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def run_gpu(h_u16, Wsub_dev, d2t_dev, k, debug=True):
+    h_dev = to_dev_bf16(h_u16)
+    R = h_u16.shape[0]
+    Vd = Wsub_dev.shape[0]
+    logits = torch.full((R, Vd), float("nan"), dtype=torch.float32, device=DEV) if debug else None
+    lse = torch.full((R,), float("nan"), dtype=torch.float32, device=DEV) if debug else None
+    ids, lp = vt.vt_draft_head(h_dev, Wsub_dev, d2t_dev, k, logits_out=logits, lse_out=lse)
+    torch.cuda.synchronize()
+    return (ids.cpu().numpy(), lp.cpu().numpy(), None if logits is None else logits.cpu().numpy(),
+            None if lse is None else lse.cpu().numpy())
+
+
+def build_both(W_u16, ids_np):
+    W_dev = to_dev_bf16(W_u16)
+    ids_dev = torch.from_numpy(ids_np).to(DEV)
+    Wsub_dev, d2t_dev = vt.vt_build_subset(W_dev, ids_dev)
+    torch.cuda.synchronize()
+    Wsub_o, d2t_o = vo.build_subset(W_u16, ids_np)
+    assert np.array_equal(dev_bits(Wsub_dev), Wsub_o), "gather is not bit-exact"
+    assert np.array_equal(d2t_dev.cpu().numpy(), d2t_o), "d2t differs"
+    return Wsub_dev, d2t_dev, Wsub_o, d2t_o
+
+
+SMALL = [
+    # rows, H, V, Vd, k           streaming regime
+    (1, 64, 300, 77, 1),
+    (1, 2048, 6000, 4096, 1),
+    (2, 520, 3000, 1001, 5),
+    (3, 1024, 9000, 4099, 10),
+    (4, 2048, 7000, 5003, 10),
+    (7, 264, 2000, 1500, 3),
+    (8, 2048, 12000, 9001, 16),
+    (13, 512, 3000, 2049, 33),
+    (16, 1024, 2000, 777, 64),
+    (1, 4096, 40000, 33001, 10),
+    # MFMA regime
+    (17, 256, 1000, 300, 8),
+    (33, 64, 500, 129, 1),
+    (130, 512, 2000, 700, 16),
+    (200, 1096, 3000, 1000, 8),
+    (260, 264, 2000, 520, 33),
+    (300, 1024, 3000, 1300, 64),
+    (512, 512, 2000, 1030, 8),
+]
+
+
+@pytest.mark.parametrize("rows,H,V,Vd,k", SMALL)
+def test_small_cases_full_comparison(rows, H, V, Vd, k):
+    _say("case rows=%d H=%d V=%d Vd=%d k=%d" % (rows, H, V, Vd, k))
+    seed = rows * 1000 + k
+    W = synth.gen_W(seed, V, H, std=0.05)
+    h = synth.gen_h(seed, rows, H, peaked_frac=0.1 if rows >= 10 else 0.0)
+    ids = synth.zipf_subset(seed, V, Vd)
+    Wsub_dev, d2t_dev, Wsub_o, d2t_o = build_both(W, ids)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, k)
+    ora = vo.draft_head(h, Wsub_o, d2t_o, k)
+    st = check_head(g_ids, g_lp, ora, d2t_o, gpu_logits=g_z, gpu_lse=g_lse)
+    _say("  %s" % st)
+    # the timed entry point (no logits stored) gives the same answer as the test hook
+    n_ids, n_lp, _, _ = run_gpu(h, Wsub_dev, d2t_dev, k, debug=False)
+    assert np.array_equal(n_ids, g_ids) and np.array_equal(n_lp, g_lp)
+
+
+@pytest.mark.parametrize("rows", [1, 5, 16, 40, 300])
+def test_exact_arithmetic_cases_are_bit_exact(rows):
+    """Small-integer inputs: every fp32 sum is exact in any order, ties abound, so logits, ids
+    and their order must equal the oracle's bit for bit (stresses the tie rule across lanes,
+    waves, tiles and workgroups)."""
+    H, Vd, k = 512, 3001, 12
+    _say("exact rows=%d" % rows)
+    Wb = synth.small_int_bf16(5, 0, (Vd, H))
+    hb = synth.small_int_bf16(5, 1, (rows, H))
+    d2t = np.arange(Vd, dtype=np.int32)[::-1].copy()  # a non-trivial map
+    W_dev = to_dev_bf16(Wb)
+    d2t_dev = torch.from_numpy(d2t).to(DEV)
+    g_ids, g_lp, g_z, g_lse = run_gpu(hb, W_dev, d2t_dev, k)
+    ora = vo.draft_head(hb, Wb, d2t, k)
+    assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
+    assert np.array_equal(g_ids, ora.ids)
+    assert np.max(np.abs(g_lp - ora.logp)) < 1e-3
+
+
+@pytest.mark.parametrize("rows", [1, 8, 64])
+def test_one_hot_hidden_state_is_bit_exact(rows):
+    H, Vd, k = 1024, 2500, 7
+    W = synth.gen_W(9, Vd, H, std=0.05)
+    h = np.zeros((rows, H), dtype=np.uint16)
+    for r in range(rows):
+        h[r, (r * 37 + 5) % H] = synth.f32_to_bf16(np.array([(-1.0) ** r * (0.5 + r)], dtype=np.float32))[0]
+    d2t = np.arange(Vd, dtype=np.int32)
+    g_ids, g_lp, g_z, _ = run_gpu(h, to_dev_bf16(W), torch.from_numpy(d2t).to(DEV), k)
+    ora = vo.draft_head(h, W, d2t, k)
+    assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
+    assert np.array_equal(g_ids, ora.ids)
+
+
+@pytest.mark.parametrize("rows", [1, 4, 100])
+def test_zero_hidden_state(rows):
+    H, Vd, k = 256, 1234, 9
+    W = synth.gen_W(2, Vd, H)
+    d2t = (np.arange(Vd, dtype=np.int32) * 3 + 1)
+    h = np.zeros((rows, H), dtype=np.uint16)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, to_dev_bf16(W), torch.from_numpy(d2t).to(DEV), k)
+    assert np.all(g_z == 0.0)
+    assert np.array_equal(g_ids, np.tile(d2t[:k], (rows, 1)))
+    assert np.allclose(g_lp, -np.log(float(Vd)), atol=1e-5)
+
+
+def test_identity_subset_and_unsorted_ids():
+    V, H = 1500, 256
+    W = synth.gen_W(4, V, H, std=0.05)
+    W[100] = W[900]
+    W[40] = W[900]
+    h = synth.gen_h(4, 3, H)
+    ident = np.arange(V, dtype=np.int32)
+    Wsub_dev, d2t_dev, Wsub_o, d2t_o = build_both(W, ident)
+    assert np.array_equal(dev_bits(Wsub_dev), W)
+    g_ids, g_lp, g_z, _ = run_gpu(h, Wsub_dev, d2t_dev, 10)
+    check_head(g_ids, g_lp, vo.draft_head(h, Wsub_o, d2t_o, 10), d2t_o, gpu_logits=g_z)
+    # unsorted ids: the position in the list is the draft index and decides ties
+    ids = np.array([900, 7, 100, 1499, 40, 0, 650], dtype=np.int32)
+    Wsub_dev, d2t_dev, Wsub_o, d2t_o = build_both(W, ids)
+    g_ids, g_lp, g_z, _ = run_gpu(h, Wsub_dev, d2t_dev, 7)
+    ora = vo.draft_head(h, Wsub_o, d2t_o, 7)
+    assert np.array_equal(g_ids, ora.ids)
+    for r in range(3):
+        pos = {int(t): p for p, t in enumerate(g_ids[r])}
+        assert pos[900] < pos[100] < pos[40]
+
+
+def test_build_subset_rejects_bad_ids_and_leaves_outputs_alone():
+    V, H = 500, 64
+    W_dev = to_dev_bf16(synth.gen_W(1, V, H))
+    out_W = torch.full((3, H), 7, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    out_d = torch.full((3,), -5, dtype=torch.int32, device=DEV)
+    for bad, code in (([1, 2, 500], 4), ([1, -1, 2], 4), ([9, 2, 9], 5)):
+        ids = torch.tensor(bad, dtype=torch.int32, device=DEV)
+        with pytest.raises(vt.VtError) as e:
+            vt.vt_build_subset(W_dev, ids, out_W, out_d)
+        assert e.value.status == code
+        torch.cuda.synchronize()
+        assert torch.all(out_d == -5) and torch.all(out_W.view(torch.int16) == 7)
+
+
+def test_results_do_not_depend_on_run(capsys):
+    rows, H, Vd, k = 6, 1024, 20011, 10
+    W = synth.gen_W(12, Vd, H)
+    h = synth.gen_h(12, rows, H)
+    W_dev, d2t_dev = to_dev_bf16(W), torch.arange(Vd, dtype=torch.int32, device=DEV)
+    a = run_gpu(h, W_dev, d2t_dev, k)
+    for _ in range(3):
+        b = run_gpu(h, W_dev, d2t_dev, k)
+        assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+        assert np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
+
+
+# ------------------------------------------------------------------ full-size workloads
+@pytest.fixture(scope="module")
+def W2048():
+    _say("generating W[128256,2048]")
+    W = synth.gen_W(0, synth.FULL_VOCAB, 2048)
+    return W, to_dev_bf16(W)
+
+
+@pytest.fixture(scope="module")
+def W4096():
+    _say("generating W[128256,4096]")
+    W = synth.gen_W(0, synth.FULL_VOCAB, 4096)
+    return W, to_dev_bf16(W)
+
+
+def _subset(W_pair, Vd):
+    W, W_dev = W_pair
+    ids = synth.zipf_subset(0, synth.FULL_VOCAB, Vd)
+    ids_dev = torch.from_numpy(ids).to(DEV)
+    Wsub_dev, d2t_dev = vt.vt_build_subset(W_dev, ids_dev)
+    torch.cuda.synchronize()
+    # gather parity at full size on sampled rows plus d2t in full
+    assert np.array_equal(d2t_dev.cpu().numpy(), ids)
+    pick = np.unique(np.concatenate([[0, Vd - 1], np.linspace(0, Vd - 1, 257).astype(np.int64)]))
+    got = dev_bits(Wsub_dev[torch.from_numpy(pick).to(DEV)])
+    assert np.array_equal(got, W[ids[pick]])
+    return ids, Wsub_dev, d2t_dev
+
+
+def test_cfg0_trimmed_head_one_row(W2048):
+    ids, Wsub_dev, d2t_dev = _subset(W2048, 4096)
+    h = synth.gen_h(0, 1, 2048)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, 1)
+    ora = vo.draft_head(h, W2048[0][ids], ids, 1)
+    _say("cfg0 %s" % check_head(g_ids, g_lp, ora, ids, gpu_logits=g_z, gpu_lse=g_lse))
+
+
+@pytest.mark.parametrize("B", [1, 4, 8])
+def test_cfg1_untrimmed_baseline_head(W2048, B):
+    ids, Wsub_dev, d2t_dev = _subset(W2048, synth.FULL_VOCAB)
+    h = synth.gen_h(0, B, 2048)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, 10)
+    ora = vo.draft_head(h, W2048[0], ids, 10)
+    _say("cfg1 B=%d %s" % (B, check_head(g_ids, g_lp, ora, ids, gpu_logits=g_z, gpu_lse=g_lse)))
+
+
+@pytest.mark.parametrize("Vd", [4096, 8192, 16384, 32768, 65536, 128256])
+def test_cfg2_vocab_sweep(W4096, Vd):
+    ids, Wsub_dev, d2t_dev = _subset(W4096, Vd)
+    h = synth.gen_h(0, 1, 4096)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, 10)
+    ora = vo.draft_head(h, W4096[0][ids], ids, 10)
+    _say("cfg2 Vd=%d %s" % (Vd, check_head(g_ids, g_lp, ora, ids, gpu_logits=g_z, gpu_lse=g_lse)))
+
+
+def _sampled_rows_check(name, W_pair, Vd, rows, k, peaked, n_sample=12):
+    ids, Wsub_dev, d2t_dev = _subset(W_pair, Vd)
+    h = synth.gen_h(0, rows, 4096, peaked_frac=peaked)
+    # the launch configuration that is timed: all rows, no logits stored
+    g_ids, g_lp, _, _ = run_gpu(h, Wsub_dev, d2t_dev, k, debug=False)
+    sample = np.unique(np.concatenate([[0, rows - 1], np.linspace(0, rows - 1, n_sample).astype(np.int64),
+                                       synth.peaked_rows(0, rows, peaked)[:4]])).astype(np.int64)
+    ora = vo.draft_head(h[sample], W_pair[0][ids], ids, k)
+    st = check_head(g_ids[sample], g_lp[sample], ora, ids)
+    _say("%s sampled rows %s: %s" % (name, list(sample), st))
+    # properties that hold for every row at any size
+    assert np.all(np.diff(g_lp, axis=1) <= 0) and np.all(g_lp <= 0)
+    member = np.zeros(synth.FULL_VOCAB, dtype=bool)
+    member[ids] = True
+    assert member[g_ids].all()
+    assert all(len(set(row)) == k for row in g_ids.tolist())
+
+
+def test_cfg3_tree_drafting_batch(W4096):
+    _sampled_rows_check("cfg3", W4096, 32000, 1024, 8, 0.0)
+
+
+def test_cfg4_large_batch_full_vocab(W4096):
+    _sampled_rows_check("cfg4", W4096, synth.FULL_VOCAB, 512, 16, 0.05)
