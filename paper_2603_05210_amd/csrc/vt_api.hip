@@ -44,7 +44,7 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         p.P = blocks;
     } else {
         p.regime = 1;
-        p.tile = gemm_pick_tile((int)rows, (int)Vd, p.KP);
+        p.tile = gemm_pick_tile((int)rows, (int)H, (int)Vd, p.KP);
         int BMV, BNR, ppv;
         gemm_tile_dims(p.tile, BMV, BNR, ppv);
         p.n_vtiles = (int)((Vd + BMV - 1) / BMV);

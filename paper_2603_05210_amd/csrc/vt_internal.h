@@ -48,6 +48,27 @@ struct HeadArgs {
     float* lse_out;    // optional [rows]
 };
 
+struct GemmArgs {
+    const void* h;
+    const void* W;
+    int rows, nchunk, Vd, P;
+    int n_vtiles, n_rtiles;
+    float* part_val;
+    int32_t* part_idx;
+    float2* part_stat;
+    float* logits_out;
+};
+
+#define VT_DECL_GEMM_KP(N) hipError_t launch_gemm_kp##N(const Plan& p, const GemmArgs& ga, hipStream_t s);
+VT_DECL_GEMM_KP(1)
+VT_DECL_GEMM_KP(2)
+VT_DECL_GEMM_KP(4)
+VT_DECL_GEMM_KP(8)
+VT_DECL_GEMM_KP(16)
+VT_DECL_GEMM_KP(32)
+VT_DECL_GEMM_KP(64)
+#undef VT_DECL_GEMM_KP
+
 hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s);
@@ -56,7 +77,7 @@ hipError_t launch_gather(const uint16_t* W, int H, const int32_t* ids, int Vd, u
                          hipStream_t s);
 
 // GEMM tile shapes (vocab x rows per workgroup) and their partial counts; defined with the kernel.
-int gemm_pick_tile(int rows, int Vd, int KP);
+int gemm_pick_tile(int rows, int H, int Vd, int KP);
 void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile);
 
 }  // namespace vt
