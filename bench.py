@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--only", type=str, default=None, help="run a single named workload as the headline")
+    ap.add_argument("--shape", type=str, default=None,
+                    help="rows,H,V_draft,k: run this shape as the headline instead (exploration)")
     return ap.parse_args()
 
 
@@ -199,6 +201,10 @@ def main():
     runner = Runner(torch, vt, synth, dev)
 
     wl = workloads()
+    if args.shape:
+        r_, h_, v_, k_ = (int(x) for x in args.shape.split(","))
+        wl = [dict(name="shape_%s" % args.shape.replace(",", "x"), H=h_, rows=r_, Vd=v_, k=k_, peaked=0.0)]
+        args.only = wl[0]["name"]
     if args.only:
         wl = [w for w in wl if w["name"] == args.only]
         assert wl, "unknown workload"

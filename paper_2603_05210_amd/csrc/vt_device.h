@@ -70,6 +70,43 @@ struct TopList {
         }
     }
 
+    // Bitonic sorting network over the KP slots (KP is a power of two): best first.
+    template <int K, int J, int I>
+    __device__ __forceinline__ void sort_step()
+    {
+        if constexpr (I < KP) {
+            constexpr int l = I ^ J;
+            if constexpr (l > I) {
+                constexpr bool first_best = (I & K) == 0;
+                const bool swap = first_best ? better(v[l], i[l], v[I], i[I]) : better(v[I], i[I], v[l], i[l]);
+                const float tv = swap ? v[l] : v[I];
+                const int ti = swap ? i[l] : i[I];
+                v[l] = swap ? v[I] : v[l];
+                i[l] = swap ? i[I] : i[l];
+                v[I] = tv;
+                i[I] = ti;
+            }
+            sort_step<K, J, I + 1>();
+        }
+    }
+    template <int K, int J>
+    __device__ __forceinline__ void sort_j()
+    {
+        if constexpr (J > 0) {
+            sort_step<K, J, 0>();
+            sort_j<K, J / 2>();
+        }
+    }
+    template <int K>
+    __device__ __forceinline__ void sort_k()
+    {
+        if constexpr (K <= KP) {
+            sort_j<K, K / 2>();
+            sort_k<K * 2>();
+        }
+    }
+    __device__ __forceinline__ void sort() { sort_k<2>(); }
+
     __device__ __forceinline__ void pop()
     {
 #pragma unroll
@@ -82,20 +119,103 @@ struct TopList {
     }
 };
 
+// ---- cross-lane exchange on the VALU (DPP / permlane swaps; no LDS round trip) ----
+// xchg<OFF>(x) returns the value held by lane (l ^ OFF).  Lane mappings used (checked on
+// gfx950): quad_perm for 1 and 2; row_shl:4 / row_shr:4 under complementary bank masks for 4;
+// row_ror:8 for 8; v_permlane16_swap / v_permlane32_swap for 16 and 32.
+template <int OFF>
+__device__ __forceinline__ int xchg_i(int x, int lane)
+{
+    if constexpr (OFF == 1) {
+        return __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false);
+    } else if constexpr (OFF == 2) {
+        return __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false);
+    } else if constexpr (OFF == 4) {
+        int t = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xf, 0x5, false);
+        return __builtin_amdgcn_update_dpp(t, x, 0x114, 0xf, 0xa, false);
+    } else if constexpr (OFF == 8) {
+        return __builtin_amdgcn_update_dpp(x, x, 0x128, 0xf, 0xf, false);
+    } else if constexpr (OFF == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16) ? (int)r[0] : (int)r[1];
+    } else {
+        static_assert(OFF == 32, "exchange distance must be a power of two <= 32");
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return (lane & 32) ? (int)r[0] : (int)r[1];
+    }
+}
+template <int OFF>
+__device__ __forceinline__ float xchg_f(float x, int lane)
+{
+    return __int_as_float(xchg_i<OFF>(__float_as_int(x), lane));
+}
+
 __device__ __forceinline__ float wave_max(float x)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        x = fmaxf(x, __shfl_xor(x, off, kWave));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0xB1, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x4E, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x141, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x140, 0xf, 0xf, false)));
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+    }
     return x;
 }
 
+// Sum over the wave; every lane returns the same bits (a fixed tree: xor 1, 2, 4, 8, 16, 32).
 __device__ __forceinline__ float wave_sum(float x)
 {
-#pragma unroll
-    for (int off = 32; off >= 1; off >>= 1)
-        x += __shfl_xor(x, off, kWave);
+    const int lane = (int)__lane_id();
+    x += xchg_f<1>(x, lane);
+    x += xchg_f<2>(x, lane);
+    x += xchg_f<4>(x, lane);
+    x += xchg_f<8>(x, lane);
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
+        x = __int_as_float(r[0]) + __int_as_float(r[1]);
+    }
     return x;
+}
+
+// Best (logit, index) pair over the wave under the strict order; every lane returns it.
+__device__ __forceinline__ void wave_best(float& v, int& i)
+{
+#define VT_BEST_DPP(CTRL)                                                                                  \
+    {                                                                                                      \
+        const float ov = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false)); \
+        const int oi = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);                           \
+        const bool c = better(ov, oi, v, i);                                                               \
+        v = c ? ov : v;                                                                                    \
+        i = c ? oi : i;                                                                                    \
+    }
+    VT_BEST_DPP(0xB1)
+    VT_BEST_DPP(0x4E)
+    VT_BEST_DPP(0x141)
+    VT_BEST_DPP(0x140)
+#undef VT_BEST_DPP
+    {
+        const auto rv = __builtin_amdgcn_permlane16_swap(__float_as_int(v), __float_as_int(v), false, false);
+        const auto ri = __builtin_amdgcn_permlane16_swap(i, i, false, false);
+        const bool c = better(__int_as_float(rv[0]), (int)ri[0], __int_as_float(rv[1]), (int)ri[1]);
+        v = __int_as_float(c ? rv[0] : rv[1]);
+        i = (int)(c ? ri[0] : ri[1]);
+    }
+    {
+        const auto rv = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
+        const auto ri = __builtin_amdgcn_permlane32_swap(i, i, false, false);
+        const bool c = better(__int_as_float(rv[0]), (int)ri[0], __int_as_float(rv[1]), (int)ri[1]);
+        v = __int_as_float(c ? rv[0] : rv[1]);
+        i = (int)(c ? ri[0] : ri[1]);
+    }
 }
 
 // Softmax partial (m, s) with s = sum exp(z - m) over some set; the empty set is (-inf, 0).
@@ -141,15 +261,7 @@ __device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane
         const int hi = active ? L.i[0] : kIdxNone;
         float bv = hv;
         int bi = hi;
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) {
-            const float ov = __shfl_xor(bv, off, kWave);
-            const int oi = __shfl_xor(bi, off, kWave);
-            if (better(ov, oi, bv, bi)) {
-                bv = ov;
-                bi = oi;
-            }
-        }
+        wave_best(bv, bi);
         if (active && hi == bi && hv == bv)
             L.pop();
         if (lane == q) {
@@ -173,7 +285,7 @@ struct PairReduce {
         for (int i = 0; i < half; ++i) {
             const float keep = up ? v[i + half] : v[i];
             const float send = up ? v[i] : v[i + half];
-            v[i] = keep + __shfl_xor(send, OFF, kWave);
+            v[i] = keep + xchg_f<OFF>(send, lane);
         }
         PairReduce<half, OFF / 2>::run(v, lane);
     }
@@ -181,12 +293,15 @@ struct PairReduce {
 template <int OFF>
 struct PairReduce<1, OFF> {
     template <int NP>
-    static __device__ __forceinline__ void run(float (&v)[NP], int)
+    static __device__ __forceinline__ void run(float (&v)[NP], int lane)
     {
         float z = v[0];
-#pragma unroll
-        for (int off = OFF; off >= 1; off >>= 1)
-            z += __shfl_xor(z, off, kWave);
+        if constexpr (OFF >= 32) z += xchg_f<32>(z, lane);
+        if constexpr (OFF >= 16) z += xchg_f<16>(z, lane);
+        if constexpr (OFF >= 8) z += xchg_f<8>(z, lane);
+        if constexpr (OFF >= 4) z += xchg_f<4>(z, lane);
+        if constexpr (OFF >= 2) z += xchg_f<2>(z, lane);
+        if constexpr (OFF >= 1) z += xchg_f<1>(z, lane);
         v[0] = z;
     }
 };

@@ -16,6 +16,8 @@
 // 128 B with the piece index XOR-swizzled by (row/2)%8 so that the 16-byte fragment reads of
 // 32 different rows spread over all banks.  Two LDS stages; the next stage's global loads
 // are issued before the current stage's MFMAs.
+#include <cstdlib>
+
 #include "vt_internal.h"
 
 namespace vt {
@@ -38,6 +40,9 @@ void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 int gemm_pick_tile(int rows, int H, int Vd, int KP)
 {
     (void)Vd;
+    if (const char* e = getenv("VT_GEMM_TILE"))  // exploration override
+        if (e[0] == '0')
+            return 0;
     // the large tile has no K-tail variant and no room for long candidate lists
     if (KP > 16 || rows <= 128 || (H % 64) != 0)
         return 0;

@@ -11,6 +11,8 @@ namespace vt {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 // Compile-time loop: the body receives an integral_constant, so every register-array index
 // below is a constant before any optimisation pass runs (accumulators must stay in registers).
@@ -58,47 +60,47 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
     const int nchunk = a.nchunk;
 
     // ---- global -> register staging: thread t moves piece (t%8) of tile rows t/8 + i*RSTEP ----
+    // Addresses are a uniform tile base (advanced by 128 B per K tile) plus a 32-bit per-lane
+    // offset; rows past the end of the matrix are clamped to its last row (masked later).
     const int lrow = tid >> 3;
     const int lc = tid & 7;
-    const u32x4* gsrc[NLD];
-    const u32x4* Wp = static_cast<const u32x4*>(a.W);
-    const u32x4* hp = static_cast<const u32x4*>(a.h);
+    const size_t row_bytes = (size_t)nchunk * 16;
+    const char* w_base = static_cast<const char*>(a.W) + (size_t)v0 * row_bytes;
+    const char* h_base = static_cast<const char*>(a.h) + (size_t)r0 * row_bytes;
+    uint32_t goff[NLD];
     static_for<NLD>([&](auto I) {
         constexpr int i = decltype(I)::value;
         const int rowid = lrow + i * RSTEP;
         if constexpr (i < NLD_W) {
             int v = v0 + rowid;
-            v = v < a.Vd ? v : a.Vd - 1;
-            gsrc[i] = Wp + (size_t)v * nchunk + lc;
+            v = (v < a.Vd ? v : a.Vd - 1) - v0;
+            goff[i] = (uint32_t)v * (uint32_t)row_bytes + lc * 16;
         } else {
             int r = r0 + rowid - BMV;
-            r = r < a.rows ? r : a.rows - 1;
-            gsrc[i] = hp + (size_t)r * nchunk + lc;
+            r = (r < a.rows ? r : a.rows - 1) - r0;
+            goff[i] = (uint32_t)r * (uint32_t)row_bytes + lc * 16;
         }
     });
     const int st_off = lrow * 8 + (lc ^ ((lrow >> 1) & 7));
 
     u32x4 stage[NLD];
-    auto load_stage = [&](int kt) {
-        bool ok = true;
-        if constexpr (GUARD_K)
-            ok = (kt * 8 + lc) < nchunk;
-        static_for<NLD>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            if constexpr (GUARD_K) {
-                const u32x4 zero = {0u, 0u, 0u, 0u};
-                stage[i] = ok ? gsrc[i][kt * 8] : zero;
-            } else {
-                stage[i] = gsrc[i][kt * 8];
-            }
-        });
+    auto load_one = [&](int kt, auto I) {
+        constexpr int i = decltype(I)::value;
+        const char* base = (i < NLD_W ? w_base : h_base) + (size_t)kt * 128;
+        const u32x4* src = reinterpret_cast<const u32x4*>(base + goff[i]);
+        if constexpr (GUARD_K) {
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            stage[i] = ((kt * 8 + lc) < nchunk) ? *src : zero;
+        } else {
+            stage[i] = *src;
+        }
     };
-    auto store_stage = [&](int buf) {
-        static_for<NLD>([&](auto I) {
-            constexpr int i = decltype(I)::value;
-            smem[buf * STAGE + st_off + i * RSTEP * 8] = stage[i];
-        });
+    auto store_one = [&](u32x4* __restrict__ wr, auto I) {
+        constexpr int i = decltype(I)::value;
+        wr[st_off + i * RSTEP * 8] = stage[i];
     };
+    auto load_stage = [&](int kt) { static_for<NLD>([&](auto I) { load_one(kt, I); }); };
+    auto store_stage = [&](u32x4* __restrict__ wr) { static_for<NLD>([&](auto I) { store_one(wr, I); }); };
 
     // ---- fragment addressing ----
     const int frow = lane & 31;
@@ -113,96 +115,251 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
         static_for<16>([&](auto E) { acc[i][decltype(E)::value] = 0.0f; });
     });
 
+    // Pipeline per K tile (4 K-steps of 16): tile kt is computed from LDS buffer kt%2.
+    //   step 0: tile kt+1 (in the staging registers since the previous iteration) -> other buffer
+    //   step 1: request tile kt+2 from memory into the staging registers
+    //   one barrier between steps 2 and 3: by then every wave has issued its last read of this
+    //   buffer and finished its writes of the other one, so step 3 can already fetch the next
+    //   tile's first fragments, and the next iteration may overwrite this buffer.
+    // Fragments are double-buffered in registers: the LDS reads for K-step ks+1 are issued
+    // alongside the MFMAs of K-step ks (sched_group_barrier fixes the interleaving).
     const int KT = (nchunk + 7) >> 3;
-    load_stage(0);
-    store_stage(0);
-    __syncthreads();
+    bf16x8 af[2][SV], bfr[2][SR];
+    // fragment number f of a K-step: f < SV is the W_sub fragment of sub-tile f, else the h one
+    auto read_one = [&](const u32x4* __restrict__ rd, auto KS, auto SET, auto F) {
+        constexpr int ks = decltype(KS)::value;
+        constexpr int set = decltype(SET)::value;
+        constexpr int f = decltype(F)::value;
+        const int pc = ((ks * 2 + fhalf) ^ fsw);
+        if constexpr (f < SV)
+            af[set][f] = __builtin_bit_cast(bf16x8, rd[a_base + f * 32 * 8 + pc]);
+        else
+            bfr[set][f - SV] = __builtin_bit_cast(bf16x8, rd[b_base + (f - SV) * 32 * 8 + pc]);
+    };
+    auto read_frags = [&](const u32x4* __restrict__ rd, auto KS, auto SET) {
+        static_for<SV + SR>([&](auto F) { read_one(rd, KS, SET, F); });
+    };
+    auto mfma_one = [&](auto SET, auto M) {
+        constexpr int set = decltype(SET)::value;
+        constexpr int sv = decltype(M)::value / SR;
+        constexpr int sr = decltype(M)::value % SR;
+        acc[sv * SR + sr] =
+            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][sv], bfr[set][sr], acc[sv * SR + sr], 0, 0, 0);
+    };
+    using C0 = std::integral_constant<int, 0>;
+    using C1 = std::integral_constant<int, 1>;
+    using C2 = std::integral_constant<int, 2>;
+    using C3 = std::integral_constant<int, 3>;
+    constexpr int NMF = SV * SR;   // MFMAs per K-step
+    constexpr int NFR = SV + SR;   // fragment reads per K-step
+    static_assert(NFR <= NMF && NLD <= 2 * NMF, "a K-step must have room for its memory operations");
 
-    for (int kt = 0; kt < KT; ++kt) {
-        const int buf = kt & 1;
-        if (kt + 1 < KT)
-            load_stage(kt + 1);
-        static_for<4>([&](auto KS) {
-            constexpr int ks = decltype(KS)::value;
-            const int pc = ((ks * 2 + fhalf) ^ fsw);
-            bf16x8 af[SV], bfr[SR];
-            static_for<SV>([&](auto I) {
-                constexpr int sv = decltype(I)::value;
-                af[sv] = __builtin_bit_cast(bf16x8, smem[buf * STAGE + a_base + sv * 32 * 8 + pc]);
-            });
-            static_for<SR>([&](auto I) {
-                constexpr int sr = decltype(I)::value;
-                bfr[sr] = __builtin_bit_cast(bf16x8, smem[buf * STAGE + b_base + sr * 32 * 8 + pc]);
-            });
-            static_for<SV>([&](auto I) {
-                constexpr int sv = decltype(I)::value;
-                static_for<SR>([&](auto Jc) {
-                    constexpr int sr = decltype(Jc)::value;
-                    acc[sv * SR + sr] =
-                        __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[sv], bfr[sr], acc[sv * SR + sr], 0, 0, 0);
+    // One K-step: the MFMAs of fragment set SET, with the LDS reads of the next K-step's
+    // fragments (from rd_next into the other set) issued one per MFMA, and optionally the tile
+    // writes (2 per MFMA, after the reads) or the global loads (1-2 per MFMA).  sched_barrier
+    // pins this order; the compiler still places the s_waitcnt.
+    auto k_step = [&](auto SET, auto KSN, const u32x4* __restrict__ rd_next, auto DO_READ, u32x4* __restrict__ wr,
+                      auto DO_WRITE, int kt_load, auto DO_LOAD) {
+        constexpr int set = decltype(SET)::value;
+        constexpr bool do_read = decltype(DO_READ)::value;
+        constexpr bool do_write = decltype(DO_WRITE)::value;
+        constexpr bool do_load = decltype(DO_LOAD)::value;
+        constexpr int W0 = NMF - (NLD + 1) / 2;  // first MFMA slot that carries tile writes
+        static_for<NMF>([&](auto M) {
+            constexpr int m = decltype(M)::value;
+            mfma_one(SET, M);
+            if constexpr (do_read && m < NFR)
+                read_one(rd_next, KSN, std::integral_constant<int, set ^ 1>{}, M);
+            if constexpr (do_write && m >= W0) {
+                constexpr int i0 = (m - W0) * 2;
+                if constexpr (i0 < NLD)
+                    store_one(wr, std::integral_constant<int, i0>{});
+                if constexpr (i0 + 1 < NLD)
+                    store_one(wr, std::integral_constant<int, i0 + 1>{});
+            }
+            if constexpr (do_load) {
+                constexpr int per = (NLD + NMF - 1) / NMF;
+                static_for<per>([&](auto Q) {
+                    constexpr int i = m * per + decltype(Q)::value;
+                    if constexpr (i < NLD)
+                        load_one(kt_load, std::integral_constant<int, i>{});
                 });
-            });
+            }
+            __builtin_amdgcn_sched_barrier(0);
         });
-        if (kt + 1 < KT)
-            store_stage(buf ^ 1);
+    };
+
+    // Pipeline per K tile (4 K-steps of 16): tile kt is computed from LDS buffer kt%2.
+    //   step 0: tile kt+1 (in the staging registers since the previous iteration) -> other buffer
+    //   step 1: request tile kt+2 from memory into the staging registers
+    //   one barrier between steps 2 and 3: by then every wave has issued its last read of this
+    //   buffer and finished its writes of the other one, so step 3 can already fetch the next
+    //   tile's first fragments, and the next iteration may overwrite this buffer.
+    auto k_tile = [&](int kt, auto HAS1, auto HAS2) {
+        // The two LDS buffers never overlap: say so, or the scheduler keeps every fragment
+        // read behind the tile writes.
+        const u32x4* __restrict__ rd = smem + (kt & 1) * STAGE;
+        u32x4* __restrict__ wr = smem + ((kt & 1) ^ 1) * STAGE;
+        k_step(C0{}, C1{}, rd, std::true_type{}, wr, HAS1, 0, std::false_type{});
+        k_step(C1{}, C2{}, rd, std::true_type{}, wr, std::false_type{}, kt + 2, HAS2);
+        k_step(C0{}, C3{}, rd, std::true_type{}, wr, std::false_type{}, 0, std::false_type{});
         __syncthreads();
+        k_step(C1{}, C0{}, smem + ((kt & 1) ^ 1) * STAGE, HAS1, wr, std::false_type{}, 0, std::false_type{});
+    };
+
+    load_stage(0);
+    store_stage(smem);
+    if (KT > 1)
+        load_stage(1);
+    __syncthreads();
+    read_frags(smem, C0{}, C0{});
+    {
+        int kt = 0;
+        for (; kt + 2 < KT; ++kt)
+            k_tile(kt, std::true_type{}, std::true_type{});
+        if (kt + 1 < KT) {
+            k_tile(kt, std::true_type{}, std::false_type{});
+            ++kt;
+        }
+        k_tile(kt, std::false_type{}, std::false_type{});
     }
 
-    // ---- fused epilogue, lane-private on the accumulators ----
-    // accumulator element e of sub-tile (sv, sr): draft token v0 + wv*SV*32 + sv*32 + 8*(e/4) + 4*(lane/32) + e%4,
-    // hidden-state row r0 + wr*SR*32 + sr*32 + lane%32.
+    // ---- fused epilogue ----
+    // Accumulator element e of sub-tile (sv, sr) is draft token
+    //   v0 + wv*SV*32 + sv*32 + 8*(e/4) + 4*(lane/32) + e%4   of hidden-state row  r0 + wr*SR*32 + sr*32 + lane%32,
+    // so for a fixed sr a lane holds NE = 16*SV logits of ONE row, in ascending token order.
+    // That stream is parked in a lane-private LDS column (so that compact run-time loops can
+    // walk it; fully unrolled code over 256 accumulators does not fit the instruction cache) and
+    // reduced in two passes:
+    //   pass 1  exact KP largest VALUES of the stream (one v_med3 per list slot and element);
+    //   pass 2  sum of exp(z - max), and the (logit, token) pairs that make up those KP values:
+    //           every element above the KP-th value, plus the earliest elements equal to it
+    //           until KP are taken -- the lower-index-wins rule.
+    // The KP survivors are sorted best-first and stored as this stream's partial result.
+    __syncthreads();  // every wave is done with the operand tiles
+    constexpr int NE = SV * 16;   // elements per stream
+    constexpr int NG = NE / 4;    // 4-element groups
+    constexpr int EP_WAVE_BYTES = NE * 64 * 4 + KP * 64 * 8;
+    char* ep = reinterpret_cast<char*>(smem) + wave * EP_WAVE_BYTES;
+    f32x4* ep_val = reinterpret_cast<f32x4*>(ep);                    // [NG][64 lanes]
+    int2* ep_list = reinterpret_cast<int2*>(ep + NE * 64 * 4);        // [KP][64 lanes]
     const int tok_base = v0 + wv * SV * 32 + 4 * fhalf;
     const int part = (vt_i * WV + wv) * 2 + fhalf;
     const bool full_v = (v0 + BMV) <= a.Vd;  // no vocabulary tail inside this tile
+
     static_for<SR>([&](auto Jc) {
         constexpr int sr = decltype(Jc)::value;
         const int row = r0 + wr * SR * 32 + sr * 32 + frow;
         const bool row_ok = row < a.rows;
-        float mx = neg_inf();
+        // park the stream (tokens past the end of the vocabulary become -inf)
         static_for<SV>([&](auto I) {
             constexpr int sv = decltype(I)::value;
-            static_for<16>([&](auto E) {
-                constexpr int e = decltype(E)::value;
-                const int tok = tok_base + sv * 32 + 8 * (e >> 2) + (e & 3);
-                if (!full_v && tok >= a.Vd)
-                    acc[sv * SR + sr][e] = neg_inf();
-                mx = fmaxf(mx, acc[sv * SR + sr][e]);
+            static_for<4>([&](auto Q) {
+                constexpr int q = decltype(Q)::value;
+                f32x4 v = {acc[sv * SR + sr][4 * q], acc[sv * SR + sr][4 * q + 1], acc[sv * SR + sr][4 * q + 2],
+                           acc[sv * SR + sr][4 * q + 3]};
+                if (!full_v) {
+                    const int t0 = tok_base + sv * 32 + 8 * q;
+                    v[0] = (t0 + 0 < a.Vd) ? v[0] : neg_inf();
+                    v[1] = (t0 + 1 < a.Vd) ? v[1] : neg_inf();
+                    v[2] = (t0 + 2 < a.Vd) ? v[2] : neg_inf();
+                    v[3] = (t0 + 3 < a.Vd) ? v[3] : neg_inf();
+                }
+                ep_val[(sv * 4 + q) * 64 + lane] = v;
             });
         });
+        if (a.logits_out != nullptr && row_ok) {
+            for (int g = 0; g < NG; ++g) {
+                const f32x4 v = ep_val[g * 64 + lane];
+                const int t0 = tok_base + (g >> 2) * 32 + (g & 3) * 8;
+                for (int c = 0; c < 4; ++c)
+                    if (t0 + c < a.Vd)
+                        a.logits_out[(size_t)row * a.Vd + t0 + c] = v[c];
+            }
+        }
+        // pass 1: KP largest values, best first
+        float top[KP];
+        static_for<KP>([&](auto S) { top[decltype(S)::value] = neg_inf(); });
+#pragma unroll 2
+        for (int g = 0; g < NG; ++g) {
+            const f32x4 v = ep_val[g * 64 + lane];
+            static_for<4>([&](auto C) {
+                const float x = v[decltype(C)::value];
+                static_for<KP - 1>([&](auto S) {
+                    constexpr int sl = KP - 1 - decltype(S)::value;  // KP-1 .. 1, old neighbours still intact
+                    top[sl] = __builtin_amdgcn_fmed3f(top[sl - 1], x, top[sl]);
+                });
+                top[0] = fmaxf(top[0], x);
+            });
+        }
+        const float mx = top[0];
+        const float thr = top[KP - 1];
+        int quota = KP;  // how many elements equal to thr belong to the KP best
+        static_for<KP>([&](auto S) { quota -= (top[decltype(S)::value] > thr) ? 1 : 0; });
+        const float mref = mx > neg_inf() ? mx : 0.0f;  // an all-masked stream sums exp(-inf) = 0
+        // pass 2
+        float ssum = 0.0f;
+        int cnt = 0;
+#pragma unroll 2
+        for (int g = 0; g < NG; ++g) {
+            const f32x4 v = ep_val[g * 64 + lane];
+            const int t0 = tok_base + (g >> 2) * 32 + (g & 3) * 8;
+            static_for<4>([&](auto C) {
+                constexpr int c = decltype(C)::value;
+                const float z = v[c];
+                ssum += __expf(z - mref);
+                const bool eq = (z == thr) && (quota > 0);
+                quota -= eq ? 1 : 0;
+                if (((z > thr) || eq) && cnt < KP) {
+                    const int tok = t0 + c;
+                    ep_list[cnt * 64 + lane] = make_int2(__float_as_int(z), tok < a.Vd ? tok : kIdxNone);
+                    ++cnt;
+                }
+            });
+        }
+        // a stream shorter than KP leaves slots open: close them with the empty marker
+        for (int sl = cnt; sl < KP; ++sl)
+            ep_list[sl * 64 + lane] = make_int2(__float_as_int(neg_inf()), kIdxNone);
+        // the survivors, sorted best first
         TopList<KP> L;
-        L.clear();
-        float s = 0.0f;
-        const float mref = mx > neg_inf() ? mx : 0.0f;  // all-masked stream: exp(-inf - 0) = 0
-        static_for<SV>([&](auto I) {
-            constexpr int sv = decltype(I)::value;
-            static_for<16>([&](auto E) {
-                constexpr int e = decltype(E)::value;
-                const int tok = tok_base + sv * 32 + 8 * (e >> 2) + (e & 3);
-                const float z = acc[sv * SR + sr][e];
-                s += __expf(z - mref);
-                L.insert_ordered(z, (full_v || tok < a.Vd) ? tok : kIdxNone);
-                if (a.logits_out != nullptr && row_ok && tok < a.Vd)
-                    a.logits_out[(size_t)row * a.Vd + tok] = z;
-            });
+        static_for<KP>([&](auto S) {
+            constexpr int sl = decltype(S)::value;
+            const int2 e = ep_list[sl * 64 + lane];
+            L.v[sl] = __int_as_float(e.x);
+            L.i[sl] = e.y;
         });
+        L.sort();
         if (row_ok) {
             const size_t slot = (size_t)row * a.P + part;
-            static_for<KP>([&](auto Q) {
-                constexpr int q = decltype(Q)::value;
-                a.part_val[slot * KP + q] = L.v[q];
-                a.part_idx[slot * KP + q] = L.i[q];
-            });
-            a.part_stat[slot] = make_float2(mx, s);
+            if constexpr (KP >= 4) {
+                static_for<KP / 4>([&](auto Q) {
+                    constexpr int q = decltype(Q)::value;
+                    const f32x4 vv = {L.v[4 * q], L.v[4 * q + 1], L.v[4 * q + 2], L.v[4 * q + 3]};
+                    const i32x4 ii = {L.i[4 * q], L.i[4 * q + 1], L.i[4 * q + 2], L.i[4 * q + 3]};
+                    reinterpret_cast<f32x4*>(a.part_val + slot * KP)[q] = vv;
+                    reinterpret_cast<i32x4*>(a.part_idx + slot * KP)[q] = ii;
+                });
+            } else {
+                static_for<KP>([&](auto Q) {
+                    constexpr int q = decltype(Q)::value;
+                    a.part_val[slot * KP + q] = L.v[q];
+                    a.part_idx[slot * KP + q] = L.i[q];
+                });
+            }
+            a.part_stat[slot] = make_float2(mx, ssum);
         }
     });
 }
-
 
 template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD>
 static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
 {
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
-    const size_t lds = (size_t)2 * (BMV + BNR) * 128;
+    const size_t lds_loop = (size_t)2 * (BMV + BNR) * 128;                              // two operand stages
+    const size_t lds_epi = (size_t)(NT / 64) * ((size_t)SV * 16 * 64 * 4 + (size_t)KP * 64 * 8);  // epilogue columns
+    const size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
+    static_assert((size_t)(NT / 64) * ((size_t)SV * 16 * 64 * 4 + (size_t)KP * 64 * 8) <= 160 * 1024,
+                  "epilogue staging must fit the LDS");
     const bool guard = (p.H % 64) != 0;
     void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false>;
     if constexpr (ALLOW_GUARD) {
