@@ -30,18 +30,24 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
     p.Vd = (int)Vd;
     p.k = k;
     p.KP = next_pow2(k);
-    if (rows <= kGemvMaxRows) {
-        p.regime = 0;
+    bool streaming = rows <= kGemvMaxRows;
+    if (streaming) {
         p.NR = next_pow2((int)rows);
-        p.J = 4;
-        const int ngroups = (int)((Vd + p.J - 1) / p.J);
-        int blocks = (ngroups + kGemvWaves - 1) / kGemvWaves;
-        if (blocks > kGemvMaxBlocks)
-            blocks = kGemvMaxBlocks;
-        if (blocks < 1)
-            blocks = 1;
-        p.blocks = blocks;
-        p.P = blocks;
+        p.J = p.NR >= 16 ? 2 : 4;
+        int rpb = (int)((Vd + kGemvTargetBlocks - 1) / kGemvTargetBlocks);
+        rpb = (rpb + 7) / 8 * 8;
+        if (rpb > kGemvMaxRowsPerBlock)
+            rpb = kGemvMaxRowsPerBlock;
+        p.rpb = rpb;
+        // hidden states and the range's logits live in LDS; very wide rows go to the other regime
+        const size_t lds = (size_t)p.NR * (size_t)H * 2 + (size_t)p.NR * rpb * 4;
+        if (lds > (size_t)kGemvLdsLimit)
+            streaming = false;
+    }
+    if (streaming) {
+        p.regime = 0;
+        p.blocks = (int)((Vd + p.rpb - 1) / p.rpb);
+        p.P = p.blocks;
     } else {
         p.regime = 1;
         p.tile = gemm_pick_tile((int)rows, (int)H, (int)Vd, p.KP);
@@ -174,7 +180,10 @@ int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k)
 {
     if (!shape_ok(rows, H, V_draft) || k < 1 || k > VT_MAX_K || k > V_draft)
         return -1;
-    return rows <= kGemvMaxRows ? 0 : 1;
+    Plan p;
+    if (!make_plan(rows, H, V_draft, k, p))
+        return -1;
+    return p.regime;
 }
 
 vt_status vt_build_subset(const uint16_t* full_W, int64_t V, int64_t H, const int32_t* token_ids, int64_t V_draft,

@@ -1,51 +1,74 @@
 // Streaming regime of the draft head (1..16 hidden-state rows): the projection of Section
 // 2.3 of the paper, z[r,j] = sum_i h[r,i] W_sub[j,i], is bound by reading W_sub once from
 // HBM (2*H*V_draft bytes, the same number as the paper's 2dk FLOP count), so the kernel is a
-// row-split dot product: a wave reads J consecutive W_sub rows with one coalesced 128-bit
-// load per lane per KiB, multiplies them against the hidden states held in LDS, and reduces
-// across its 64 lanes with shuffles.  Softmax statistics and the k best candidates are kept
-// per lane while streaming, merged per workgroup at the end, and one partial per (row,
-// workgroup) goes to the merge kernel.  Logits never reach memory (except in the test hook).
+// row-split dot product.
+//
+// A workgroup of 16 waves owns a contiguous range of at most kGemvMaxRowsPerBlock W_sub rows.
+// A wave reads J consecutive rows at a time, one coalesced 128-bit load per lane per KiB,
+// multiplies them against the hidden states held in LDS (bf16 pairs through v_dot2_f32_bf16,
+// fp32 accumulation) and reduces across its 64 lanes on the VALU (DPP / permlane swaps).  The
+// logits of the range are parked in LDS, never in memory (except in the test hook).  When the
+// range is done, wave r reduces hidden-state row r: softmax statistics and the k best logits
+// of the range by k rounds of a wave-wide arg-max under the (logit, lower index) order.  One
+// partial per (row, workgroup) goes to the merge kernel.
 #include "vt_device.h"
 #include "vt_internal.h"
 
 namespace vt {
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
 struct GemvArgs {
     const u32x4* h;
     const u32x4* W;
-    int rows, nchunk, Vd, P;
+    int rows, nchunk, Vd, P, k, KP, rpb;  // rpb: W_sub rows per workgroup (multiple of J)
     float* part_val;
     int32_t* part_idx;
     float2* part_stat;
     float* logits_out;
 };
 
+template <bool DOT2>
 __device__ __forceinline__ float dot8(const u32x4& w, const u32x4& x, float acc)
 {
-    acc = fmaf(bf16_lo(w.x), bf16_lo(x.x), acc);
-    acc = fmaf(bf16_hi(w.x), bf16_hi(x.x), acc);
-    acc = fmaf(bf16_lo(w.y), bf16_lo(x.y), acc);
-    acc = fmaf(bf16_hi(w.y), bf16_hi(x.y), acc);
-    acc = fmaf(bf16_lo(w.z), bf16_lo(x.z), acc);
-    acc = fmaf(bf16_hi(w.z), bf16_hi(x.z), acc);
-    acc = fmaf(bf16_lo(w.w), bf16_lo(x.w), acc);
-    acc = fmaf(bf16_hi(w.w), bf16_hi(x.w), acc);
+    if constexpr (DOT2) {
+        // (cast the whole 128-bit vector, then pick pairs: a bit_cast of a single component of
+        // an ext_vector reads component 0 with this compiler)
+        const bf16x8 wb = __builtin_bit_cast(bf16x8, w);
+        const bf16x8 xb = __builtin_bit_cast(bf16x8, x);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(wb, wb, 0, 1), __builtin_shufflevector(xb, xb, 0, 1), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(wb, wb, 2, 3), __builtin_shufflevector(xb, xb, 2, 3), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(wb, wb, 4, 5), __builtin_shufflevector(xb, xb, 4, 5), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(wb, wb, 6, 7), __builtin_shufflevector(xb, xb, 6, 7), acc, false);
+    } else {
+        acc = fmaf(bf16_lo(w.x), bf16_lo(x.x), acc);
+        acc = fmaf(bf16_hi(w.x), bf16_hi(x.x), acc);
+        acc = fmaf(bf16_lo(w.y), bf16_lo(x.y), acc);
+        acc = fmaf(bf16_hi(w.y), bf16_hi(x.y), acc);
+        acc = fmaf(bf16_lo(w.z), bf16_lo(x.z), acc);
+        acc = fmaf(bf16_hi(w.z), bf16_hi(x.z), acc);
+        acc = fmaf(bf16_lo(w.w), bf16_lo(x.w), acc);
+        acc = fmaf(bf16_hi(w.w), bf16_hi(x.w), acc);
+    }
     return acc;
 }
 
-template <int NR, int J, int KP>
+template <int NR, int J, bool DOT2>
 __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
 {
-    constexpr int NP = NR * J;               // (row, W_sub row) pairs reduced together
-    constexpr int CL = kWave / NP;           // lanes that end up holding the same pair
+    constexpr int NP = NR * J;      // (hidden row, W_sub row) pairs reduced together
+    constexpr int CL = kWave / NP;  // lanes that end up holding the same pair
+    constexpr int VPL = kGemvMaxRowsPerBlock / kWave;  // logits per lane in the selection
     static_assert(NP <= kWave && (NP & (NP - 1)) == 0, "pairs per group must be a power of two <= 64");
+    static_assert(NR <= kGemvWaves, "one wave per hidden-state row in the selection");
     extern __shared__ u32x4 smem[];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int nchunk = a.nchunk;
+    float* zbuf = reinterpret_cast<float*>(smem + NR * nchunk);  // [NR][rpb]
 
     // hidden states -> LDS (rows beyond `rows` repeat the last one; their results are dropped)
     for (int x = tid; x < NR * nchunk; x += kGemvThreads) {
@@ -61,122 +84,140 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
     const int jj_l = p_l - r_l * J;
     const bool owner = (lane & (CL - 1)) == 0;
 
-    TopList<KP> L;
-    L.clear();
-    float m = neg_inf(), s = 0.0f;
+    const int j_lo = blockIdx.x * a.rpb;
+    const int j_hi = (j_lo + a.rpb < a.Vd) ? j_lo + a.rpb : a.Vd;
+    const int n_local = j_hi - j_lo;
+    const int ngroups = (n_local + J - 1) / J;
 
-    const int ngroups = (a.Vd + J - 1) / J;
-    const int gw = blockIdx.x * kGemvWaves + wave;
-    const int nw = gridDim.x * kGemvWaves;
-
-    for (int g = gw; g < ngroups; g += nw) {
-        const int j0 = g * J;
-        const u32x4* wp[J];
+    // The wave walks positions (group g of J rows, 1 KiB column step t) in order and keeps the
+    // loads of the next position in flight while it multiplies the current one, also across
+    // the boundary between two groups.
+    const int T = (nchunk + kWave - 1) / kWave;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    auto load_pos = [&](int gg, int tt, u32x4(&buf)[J]) {
+        const int c = lane + tt * kWave;
+        const int j0 = j_lo + gg * J;
 #pragma unroll
         for (int jj = 0; jj < J; ++jj) {
             const int j = (j0 + jj < a.Vd) ? j0 + jj : a.Vd - 1;
-            wp[jj] = a.W + (size_t)j * nchunk;
+            buf[jj] = (c < nchunk) ? __builtin_nontemporal_load(a.W + (size_t)j * nchunk + c) : zero4;
         }
-        float acc[NR][J];
+    };
+    float acc[NR][J];
 #pragma unroll
-        for (int r = 0; r < NR; ++r)
+    for (int r = 0; r < NR; ++r)
 #pragma unroll
-            for (int jj = 0; jj < J; ++jj)
-                acc[r][jj] = 0.0f;
+        for (int jj = 0; jj < J; ++jj)
+            acc[r][jj] = 0.0f;
 
-#pragma unroll 2
-        for (int c = lane; c < nchunk; c += kWave) {
-            u32x4 w[J];
+    int g = wave, t = 0;
+    auto step = [&](u32x4(&cur)[J], u32x4(&nxt)[J]) {
+        int tn = t + 1, gn = g;
+        if (tn == T) {
+            tn = 0;
+            gn = g + kGemvWaves;
+        }
+        if (gn < ngroups)
+            load_pos(gn, tn, nxt);
+        int c = lane + t * kWave;
+        c = c < nchunk ? c : nchunk - 1;  // lanes past the row end hold zeros in cur
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const u32x4 x = smem[r * nchunk + c];
 #pragma unroll
             for (int jj = 0; jj < J; ++jj)
-                w[jj] = __builtin_nontemporal_load(wp[jj] + c);
+                acc[r][jj] = dot8<DOT2>(cur[jj], x, acc[r][jj]);
+        }
+        if (t == T - 1) {
+            float pv[NP];
 #pragma unroll
-            for (int r = 0; r < NR; ++r) {
-                const u32x4 x = smem[r * nchunk + c];
+            for (int r = 0; r < NR; ++r)
 #pragma unroll
-                for (int jj = 0; jj < J; ++jj)
-                    acc[r][jj] = dot8(w[jj], x, acc[r][jj]);
+                for (int jj = 0; jj < J; ++jj) {
+                    pv[r * J + jj] = acc[r][jj];
+                    acc[r][jj] = 0.0f;
+                }
+            const float z = reduce_pairs<NP>(pv, lane);
+            const int j = j_lo + g * J + jj_l;
+            if (owner && j < j_hi && r_l < a.rows) {
+                zbuf[r_l * a.rpb + (j - j_lo)] = z;
+                if (a.logits_out != nullptr)
+                    a.logits_out[(size_t)r_l * a.Vd + j] = z;
             }
         }
-
-        float pv[NP];
-#pragma unroll
-        for (int r = 0; r < NR; ++r)
-#pragma unroll
-            for (int jj = 0; jj < J; ++jj)
-                pv[r * J + jj] = acc[r][jj];
-        float z = reduce_pairs<NP>(pv, lane);
-
-        const int j = j0 + jj_l;
-        const bool valid = (j < a.Vd) && (r_l < a.rows);
-        if (!valid)
-            z = neg_inf();
-        if (a.logits_out != nullptr && valid && owner)
-            a.logits_out[(size_t)r_l * a.Vd + j] = z;
-        stat_add(m, s, z);
-        L.insert_ordered(z, valid ? j : kIdxNone);
-    }
-
-    // ---- per-workgroup merge: lanes -> wave (registers), waves -> workgroup (LDS) ----
-    __syncthreads();  // the hidden states in LDS are dead from here on
-    float* sm_val = reinterpret_cast<float*>(smem);                  // [waves][NR][KP]
-    int* sm_idx = reinterpret_cast<int*>(sm_val + kGemvWaves * NR * KP);
-    float2* sm_stat = reinterpret_cast<float2*>(sm_idx + kGemvWaves * NR * KP);  // [waves][NR]
-
-#pragma unroll 1
-    for (int r = 0; r < NR; ++r) {
-        const bool act = owner && (r_l == r);
-        float mv = m, sv = s;
-        wave_stat_merge(mv, sv, act);
-        float ov;
-        int oi;
-        wave_merge<KP>(L, act, lane, ov, oi);
-        if (lane < KP) {
-            sm_val[(wave * NR + r) * KP + lane] = ov;
-            sm_idx[(wave * NR + r) * KP + lane] = oi;
-        }
-        if (lane == 0)
-            sm_stat[wave * NR + r] = make_float2(mv, sv);
+        t = tn;
+        g = gn;
+    };
+    u32x4 bufA[J], bufB[J];
+    if (g < ngroups)
+        load_pos(g, 0, bufA);
+    while (g < ngroups) {
+        step(bufA, bufB);
+        if (g >= ngroups)
+            break;
+        step(bufB, bufA);
     }
     __syncthreads();
 
-    for (int r = wave; r < a.rows; r += kGemvWaves) {
-        const bool act = lane < kGemvWaves;
-        TopList<KP> T;
-        T.clear();
-        float mv = neg_inf(), sv = 0.0f;
-        if (act) {
+    // ---- selection over this workgroup's range: wave r handles hidden-state row r ----
+    if (wave < a.rows) {
+        const int r = wave;
+        float v[VPL];
+        float mloc = neg_inf();
 #pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                T.v[q] = sm_val[(lane * NR + r) * KP + q];
-                T.i[q] = sm_idx[(lane * NR + r) * KP + q];
-            }
-            const float2 st = sm_stat[lane * NR + r];
-            mv = st.x;
-            sv = st.y;
+        for (int i = 0; i < VPL; ++i) {
+            const int e = lane + i * kWave;
+            v[i] = (e < n_local) ? zbuf[r * a.rpb + e] : neg_inf();
+            mloc = fmaxf(mloc, v[i]);
         }
-        wave_stat_merge(mv, sv, act);
-        float ov;
-        int oi;
-        wave_merge<KP>(T, act, lane, ov, oi);
+        const float m = wave_max(mloc);
+        float sloc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < VPL; ++i)
+            sloc += __expf(v[i] - m);  // n_local >= 1, so m is finite
+        const float s = wave_sum(sloc);
+
+        float outv = neg_inf();
+        int outi = kIdxNone;
+#pragma unroll 1
+        for (int q = 0; q < a.k; ++q) {
+            // best of this lane's logits: the first maximum has the lowest index
+            float bv = v[0];
+            int bi = 0;
+#pragma unroll
+            for (int i = 1; i < VPL; ++i) {
+                const bool c = v[i] > bv;
+                bv = c ? v[i] : bv;
+                bi = c ? i : bi;
+            }
+            int gi = (bv > neg_inf()) ? (j_lo + lane + bi * kWave) : kIdxNone;
+            wave_best(bv, gi);
+            if (lane == q) {
+                outv = bv;
+                outi = gi;
+            }
+            // the owner retires the winner
+            const int mine = gi - j_lo - lane;  // = i * 64 for the owner's slot i
+#pragma unroll
+            for (int i = 0; i < VPL; ++i)
+                v[i] = (mine == i * kWave) ? neg_inf() : v[i];
+        }
         const size_t slot = (size_t)r * a.P + blockIdx.x;
-        if (lane < KP) {
-            a.part_val[slot * KP + lane] = ov;
-            a.part_idx[slot * KP + lane] = oi;
+        if (lane < a.KP) {  // slots k..KP-1 carry the empty marker
+            a.part_val[slot * a.KP + lane] = outv;
+            a.part_idx[slot * a.KP + lane] = outi;
         }
         if (lane == 0)
-            a.part_stat[slot] = make_float2(mv, sv);
+            a.part_stat[slot] = make_float2(m, s);
     }
 }
 
-template <int NR, int J, int KP>
+template <int NR, int J, bool DOT2>
 static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
-    const size_t lds_h = (size_t)NR * ga.nchunk * sizeof(u32x4);
-    const size_t lds_merge = (size_t)kGemvWaves * NR * (KP * 8 + 8);
-    const size_t lds = lds_h > lds_merge ? lds_h : lds_merge;
-    auto kern = gemv_head_kernel<NR, J, KP>;
-    if (lds > 160 * 1024)
+    const size_t lds = (size_t)NR * ga.nchunk * sizeof(u32x4) + (size_t)NR * ga.rpb * sizeof(float);
+    auto kern = gemv_head_kernel<NR, J, DOT2>;
+    if (lds > (size_t)kGemvLdsLimit)
         return hipErrorInvalidValue;
     static size_t lds_allowed = 48 * 1024;  // per instantiation: raised once, then remembered
     if (lds > lds_allowed) {
@@ -190,21 +231,6 @@ static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int NR, int J>
-static hipError_t launch_kp(const Plan& p, const GemvArgs& ga, hipStream_t s)
-{
-    switch (p.KP) {
-    case 1: return launch_one<NR, J, 1>(p, ga, s);
-    case 2: return launch_one<NR, J, 2>(p, ga, s);
-    case 4: return launch_one<NR, J, 4>(p, ga, s);
-    case 8: return launch_one<NR, J, 8>(p, ga, s);
-    case 16: return launch_one<NR, J, 16>(p, ga, s);
-    case 32: return launch_one<NR, J, 32>(p, ga, s);
-    case 64: return launch_one<NR, J, 64>(p, ga, s);
-    }
-    return hipErrorInvalidValue;
-}
-
 hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
 {
     GemvArgs ga;
@@ -214,16 +240,19 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.nchunk = p.H / 8;
     ga.Vd = p.Vd;
     ga.P = p.P;
+    ga.k = p.k;
+    ga.KP = p.KP;
+    ga.rpb = p.rpb;
     ga.part_val = a.part_val;
     ga.part_idx = a.part_idx;
     ga.part_stat = a.part_stat;
     ga.logits_out = a.logits_out;
     switch (p.NR) {
-    case 1: return launch_kp<1, 4>(p, ga, s);
-    case 2: return launch_kp<2, 4>(p, ga, s);
-    case 4: return launch_kp<4, 4>(p, ga, s);
-    case 8: return launch_kp<8, 4>(p, ga, s);
-    case 16: return launch_kp<16, 4>(p, ga, s);
+    case 1: return launch_one<1, 4, true>(p, ga, s);
+    case 2: return launch_one<2, 4, true>(p, ga, s);
+    case 4: return launch_one<4, 4, true>(p, ga, s);
+    case 8: return launch_one<8, 4, true>(p, ga, s);
+    case 16: return launch_one<16, 2, true>(p, ga, s);
     }
     return hipErrorInvalidValue;
 }

@@ -11,9 +11,11 @@ namespace vt {
 // Streaming regime (rows <= kGemvMaxRows): workgroups of kGemvThreads threads, each wave
 // streams groups of J consecutive W_sub rows.
 constexpr int kGemvMaxRows = 16;
-constexpr int kGemvThreads = 512;
+constexpr int kGemvThreads = 1024;
 constexpr int kGemvWaves = kGemvThreads / 64;
-constexpr int kGemvMaxBlocks = 512;
+constexpr int kGemvMaxRowsPerBlock = 512;  // W_sub rows one workgroup may own (8 logits per lane at the end)
+constexpr int kGemvTargetBlocks = 256;     // one workgroup per compute unit of an MI355X
+constexpr int kGemvLdsLimit = 160 * 1024;
 constexpr int kMergeThreads = 256;
 
 struct Plan {
@@ -23,6 +25,7 @@ struct Plan {
     // streaming regime
     int NR;      // rows rounded up to a power of two
     int J;       // W_sub rows a wave reduces together
+    int rpb;     // W_sub rows per workgroup
     // GEMM regime
     int tile;    // index into the table of tile shapes
     int n_vtiles, n_rtiles;

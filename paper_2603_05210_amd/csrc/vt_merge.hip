@@ -41,13 +41,24 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         stat_merge(m, s, st.x, st.y);
         const float* pv = part_val + slot * KP;
         const int32_t* pi = part_idx + slot * KP;
-#pragma unroll 1
-        for (int q = 0; q < KP; ++q) {  // partial lists are sorted: stop at the first loser
-            const float x = pv[q];
-            const int ix = pi[q];
-            if (!better(x, ix, L.v[KP - 1], L.i[KP - 1]))
-                break;
-            L.insert(x, ix);
+        if (p == tid) {  // the first list of a thread is taken as it is (partial lists are sorted)
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                L.v[q] = pv[q];
+                L.i[q] = pi[q];
+            }
+        } else if (!(st.x < L.v[KP - 1])) {  // st.x is the list's best logit: skip lists that cannot enter
+            float lv[KP];
+            int li[KP];
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                lv[q] = pv[q];
+                li[q] = pi[q];
+            }
+#pragma unroll
+            for (int q = 0; q < KP; ++q)
+                if (better(lv[q], li[q], L.v[KP - 1], L.i[KP - 1]))
+                    L.insert(lv[q], li[q]);
         }
     }
 
