@@ -48,6 +48,8 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         p.regime = 0;
         p.blocks = (int)((Vd + p.rpb - 1) / p.rpb);
         p.P = p.blocks;
+        // fusing pays while one workgroup can finish all rows in one pass
+        p.fused = (rows <= 2 && p.P <= 256 && p.KP <= 16) ? 1 : 0;
     } else {
         p.regime = 1;
         p.tile = gemm_pick_tile((int)rows, (int)H, (int)Vd, p.KP);
@@ -262,7 +264,7 @@ vt_status vt_draft_head_debug(const uint16_t* h, int64_t rows, int64_t H, const 
         return VT_ERR_DEVICE;
     if (e1 && hipEventRecord(e1, s) != hipSuccess)
         return VT_ERR_DEVICE;
-    if (launch_merge(p, a, s) != hipSuccess)
+    if (!(p.regime == 0 && p.fused) && launch_merge(p, a, s) != hipSuccess)
         return VT_ERR_DEVICE;
     return VT_OK;
 }

@@ -251,12 +251,13 @@ __device__ __forceinline__ void wave_stat_merge(float& m, float& s, bool active)
 // q-th best candidate of the union in (outv, outi).  The lists of active lanes are consumed.
 // Indices must be distinct across lists (empty slots carry kIdxNone with -inf).
 template <int KP>
-__device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane, float& outv, int& outi)
+__device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane, float& outv, int& outi,
+                                           int rounds = KP)
 {
     outv = neg_inf();
     outi = kIdxNone;
 #pragma unroll 1
-    for (int q = 0; q < KP; ++q) {
+    for (int q = 0; q < rounds; ++q) {
         const float hv = active ? L.v[0] : neg_inf();
         const int hi = active ? L.i[0] : kIdxNone;
         float bv = hv;
@@ -265,6 +266,72 @@ __device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane
         if (active && hi == bi && hv == bv)
             L.pop();
         if (lane == q) {
+            outv = bv;
+            outi = bi;
+        }
+    }
+}
+
+// ---- the same reductions inside one DPP row (16 consecutive lanes), DPP only ----
+__device__ __forceinline__ float row16_max(float x)
+{
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0xB1, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x4E, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x141, 0xf, 0xf, false)));
+    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x140, 0xf, 0xf, false)));
+    return x;
+}
+
+__device__ __forceinline__ float row16_sum(float x, int lane)
+{
+    x += xchg_f<1>(x, lane);
+    x += xchg_f<2>(x, lane);
+    x += xchg_f<4>(x, lane);
+    x += xchg_f<8>(x, lane);
+    return x;
+}
+
+__device__ __forceinline__ void row16_best(float& v, int& i)
+{
+#define VT_BEST_DPP(CTRL)                                                                                  \
+    {                                                                                                      \
+        const float ov = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false)); \
+        const int oi = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);                           \
+        const bool c = better(ov, oi, v, i);                                                               \
+        v = c ? ov : v;                                                                                    \
+        i = c ? oi : i;                                                                                    \
+    }
+    VT_BEST_DPP(0xB1)
+    VT_BEST_DPP(0x4E)
+    VT_BEST_DPP(0x141)
+    VT_BEST_DPP(0x140)
+#undef VT_BEST_DPP
+}
+
+// Combine the softmax partials of the 16 lanes of a row (inactive lanes pass (-inf, 0)).
+__device__ __forceinline__ void row16_stat_merge(float& m, float& s, int lane)
+{
+    const float M = row16_max(m);
+    const float t = (m > neg_inf()) ? s * __expf(m - M) : 0.0f;
+    s = row16_sum(t, lane);
+    m = M;
+}
+
+// Merge the sorted lists held by the 16 lanes of a row: after `rounds` (<= 16, <= KP) rounds
+// the lane with (lane % 16) == q holds the q-th best candidate of the union.  Lists are consumed.
+template <int KP>
+__device__ __forceinline__ void row16_merge(TopList<KP>& L, int rounds, int lane, float& outv, int& outi)
+{
+    outv = neg_inf();
+    outi = kIdxNone;
+#pragma unroll 1
+    for (int q = 0; q < rounds; ++q) {
+        float bv = L.v[0];
+        int bi = L.i[0];
+        row16_best(bv, bi);
+        if (L.i[0] == bi && L.v[0] == bv)
+            L.pop();
+        if ((lane & 15) == q) {
             outv = bv;
             outi = bi;
         }

@@ -11,6 +11,8 @@
 // range is done, wave r reduces hidden-state row r: softmax statistics and the k best logits
 // of the range by k rounds of a wave-wide arg-max under the (logit, lower index) order.  One
 // partial per (row, workgroup) goes to the merge kernel.
+#include <atomic>
+
 #include "vt_device.h"
 #include "vt_internal.h"
 
@@ -27,7 +29,104 @@ struct GemvArgs {
     int32_t* part_idx;
     float2* part_stat;
     float* logits_out;
+    // fused final merge (done by the last workgroup to finish) -- used when `fused` is set
+    int fused, ticket_slot;
+    const int32_t* d2t;
+    int32_t* out_ids;
+    float* out_logp;
+    float* lse_out;
 };
+
+// Arrival counters for the fused merge, one per in-flight call (the host hands out slots
+// round-robin); zero when idle: the last workgroup of a call puts its slot back to zero.
+//
+// No cache-wide fences are used: the partial results are a few hundred bytes per workgroup and
+// travel through device-coherent accesses (relaxed agent-scope atomics: they bypass the
+// per-XCD caches), ordered by "stores acknowledged -> workgroup barrier -> ticket".
+constexpr int kTicketSlots = 1024;
+__device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_dev(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+static __device__ unsigned int g_ticket[kTicketSlots];
+
+// Final merge by the last workgroup: level 1 merges the P per-workgroup partials of a row in
+// groups of 16 lists (one 16-lane DPP row per group, 64 groups at a time over the 16 waves),
+// level 2 merges the <= 16 results per row and emits ids (through d2t) and log-probabilities.
+template <int KP>
+__device__ __forceinline__ void fused_final_merge(const GemvArgs& a, char* lds, int tid)
+{
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int sub = lane & 15;
+    const int nchunks = (a.P + 15) >> 4;  // <= 16
+    const int ngroups = a.rows * nchunks;
+    float* l1_val = reinterpret_cast<float*>(lds);                 // [ngroups][KP]
+    int* l1_idx = reinterpret_cast<int*>(l1_val + ngroups * KP);   // [ngroups][KP]
+    float2* l1_stat = reinterpret_cast<float2*>(l1_idx + ngroups * KP);
+
+    for (int base = 0; base < ngroups; base += kGemvWaves * 4) {
+        const int gidx = base + wave * 4 + (lane >> 4);
+        const bool gok = gidx < ngroups;
+        const int row = gok ? gidx / nchunks : 0;
+        const int chunk = gidx - row * nchunks;
+        const int p = chunk * 16 + sub;
+        TopList<KP> L;
+        L.clear();
+        float m = neg_inf(), s = 0.0f;
+        if (gok && p < a.P) {
+            const size_t slot = (size_t)row * a.P + p;
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                L.v[q] = ld_dev(a.part_val + slot * KP + q);
+                L.i[q] = ld_dev(a.part_idx + slot * KP + q);
+            }
+            m = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot));
+            s = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot) + 1);
+        }
+        row16_stat_merge(m, s, lane);
+        float ov;
+        int oi;
+        row16_merge<KP>(L, a.k, lane, ov, oi);
+        if (gok) {
+            if (sub < KP) {
+                l1_val[gidx * KP + sub] = ov;
+                l1_idx[gidx * KP + sub] = oi;
+            }
+            if (sub == 0)
+                l1_stat[gidx] = make_float2(m, s);
+        }
+    }
+    __syncthreads();
+
+    const int row = wave * 4 + (lane >> 4);
+    if (row < a.rows) {  // whole 16-lane rows are in or out together
+        TopList<KP> L;
+        L.clear();
+        float m = neg_inf(), s = 0.0f;
+        if (sub < nchunks) {
+            const int gidx = row * nchunks + sub;
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                L.v[q] = l1_val[gidx * KP + q];
+                L.i[q] = l1_idx[gidx * KP + q];
+            }
+            m = l1_stat[gidx].x;
+            s = l1_stat[gidx].y;
+        }
+        row16_stat_merge(m, s, lane);
+        float ov;
+        int oi;
+        row16_merge<KP>(L, a.k, lane, ov, oi);
+        const float lse = m + __logf(s);
+        if (sub < a.k) {
+            a.out_ids[(size_t)row * a.k + sub] = (oi != kIdxNone) ? a.d2t[oi] : -1;
+            a.out_logp[(size_t)row * a.k + sub] = ov - lse;
+        }
+        if (sub == 0 && a.lse_out != nullptr)
+            a.lse_out[row] = lse;
+    }
+}
 
 template <bool DOT2>
 __device__ __forceinline__ float dot8(const u32x4& w, const u32x4& x, float acc)
@@ -204,18 +303,51 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
         }
         const size_t slot = (size_t)r * a.P + blockIdx.x;
         if (lane < a.KP) {  // slots k..KP-1 carry the empty marker
-            a.part_val[slot * a.KP + lane] = outv;
-            a.part_idx[slot * a.KP + lane] = outi;
+            st_dev(a.part_val + slot * a.KP + lane, outv);
+            st_dev(a.part_idx + slot * a.KP + lane, outi);
         }
-        if (lane == 0)
-            a.part_stat[slot] = make_float2(m, s);
+        if (lane == 0) {
+            st_dev(reinterpret_cast<float*>(a.part_stat + slot), m);
+            st_dev(reinterpret_cast<float*>(a.part_stat + slot) + 1, s);
+        }
+        // vmcnt(0): this wave's coherent stores are acknowledged before it reaches the barrier
+        // that precedes the ticket (expcnt / lgkmcnt fields left at their maxima)
+        __builtin_amdgcn_s_waitcnt(0x0F70);
     }
+
+    if (!a.fused)
+        return;
+    // ---- fused final merge: the last workgroup to arrive finishes the call ----
+    __shared__ int s_last;
+    __syncthreads();
+    if (tid == 0) {
+        const unsigned int t =
+            __hip_atomic_fetch_add(&g_ticket[a.ticket_slot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_last = (t == gridDim.x - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!s_last)
+        return;
+    char* lds = reinterpret_cast<char*>(smem);
+    switch (a.KP) {
+    case 1: fused_final_merge<1>(a, lds, tid); break;
+    case 2: fused_final_merge<2>(a, lds, tid); break;
+    case 4: fused_final_merge<4>(a, lds, tid); break;
+    case 8: fused_final_merge<8>(a, lds, tid); break;
+    default: fused_final_merge<16>(a, lds, tid); break;
+    }
+    if (tid == 0)
+        __hip_atomic_store(&g_ticket[a.ticket_slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int NR, int J, bool DOT2>
 static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
-    const size_t lds = (size_t)NR * ga.nchunk * sizeof(u32x4) + (size_t)NR * ga.rpb * sizeof(float);
+    size_t lds = (size_t)NR * ga.nchunk * sizeof(u32x4) + (size_t)NR * ga.rpb * sizeof(float);
+    if (ga.fused) {  // staging of the level-1 results of the fused merge
+        const size_t l1 = (size_t)ga.rows * ((ga.P + 15) / 16) * ((size_t)ga.KP * 8 + 8);
+        lds = lds > l1 ? lds : l1;
+    }
     auto kern = gemv_head_kernel<NR, J, DOT2>;
     if (lds > (size_t)kGemvLdsLimit)
         return hipErrorInvalidValue;
@@ -247,6 +379,13 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.part_idx = a.part_idx;
     ga.part_stat = a.part_stat;
     ga.logits_out = a.logits_out;
+    ga.fused = p.fused;
+    static std::atomic<unsigned int> next_slot{0};
+    ga.ticket_slot = p.fused ? (int)(next_slot.fetch_add(1u) % (unsigned int)kTicketSlots) : 0;
+    ga.d2t = a.d2t;
+    ga.out_ids = a.out_ids;
+    ga.out_logp = a.out_logp;
+    ga.lse_out = a.lse_out;
     switch (p.NR) {
     case 1: return launch_one<1, 4, true>(p, ga, s);
     case 2: return launch_one<2, 4, true>(p, ga, s);

@@ -26,6 +26,7 @@ struct Plan {
     int NR;      // rows rounded up to a power of two
     int J;       // W_sub rows a wave reduces together
     int rpb;     // W_sub rows per workgroup
+    int fused;   // the streaming kernel's last workgroup also does the final merge
     // GEMM regime
     int tile;    // index into the table of tile shapes
     int n_vtiles, n_rtiles;

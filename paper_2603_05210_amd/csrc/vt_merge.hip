@@ -65,7 +65,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
     wave_stat_merge(m, s, true);
     float ov;
     int oi;
-    wave_merge<KP>(L, true, lane, ov, oi);
+    wave_merge<KP>(L, true, lane, ov, oi, k);
     if (lane < KP) {
         sm_val[wave][lane] = ov;
         sm_idx[wave][lane] = oi;
@@ -81,15 +81,17 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         float mv = neg_inf(), sv = 0.0f;
         if (act) {
 #pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                T.v[q] = sm_val[lane][q];
-                T.i[q] = sm_idx[lane][q];
+            for (int q = 0; q < KP; ++q) {  // slots k..KP-1 were not produced: leave them empty
+                if (q < k) {
+                    T.v[q] = sm_val[lane][q];
+                    T.i[q] = sm_idx[lane][q];
+                }
             }
             mv = sm_stat[lane].x;
             sv = sm_stat[lane].y;
         }
         wave_stat_merge(mv, sv, act);
-        wave_merge<KP>(T, act, lane, ov, oi);
+        wave_merge<KP>(T, act, lane, ov, oi, k);
         const float lse = mv + __logf(sv);
         if (lane < k) {
             out_ids[(size_t)r * k + lane] = (oi != kIdxNone) ? d2t[oi] : -1;
