@@ -39,6 +39,9 @@ def parse_args():
     ap.add_argument("--no-sweep", action="store_true", help="only the headline workload")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--only", type=str, default=None, help="run a single named workload as the headline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain 1 GiB device copy a few times and exit (reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE profiler counters)")
     ap.add_argument("--shape", type=str, default=None,
                     help="rows,H,V_draft,k: run this shape as the headline instead (exploration)")
     return ap.parse_args()
@@ -169,7 +172,7 @@ def cpu_baseline(runner, w, st):
     r_use = min(rows, 8)
     h = st["h"][:r_use]
     reps, t_total = 0, 0.0
-    while t_total < 10.0 and reps < 50:
+    while t_total < 10.0 and reps < 5000:
         t0 = time.perf_counter()
         vo.draft_head(h, W_sub, ids, w["k"], want_logits=False)
         t_total += time.perf_counter() - t0
@@ -180,8 +183,48 @@ def cpu_baseline(runner, w, st):
                        % (r_use, rows, len(ids), reps, t_total))
 
 
+def kernel_source_hash():
+    """sha256 over the HIP sources: recorded with profiler counters so stale counters are not reported."""
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted((ROOT / "paper_2603_05210_amd" / "csrc").glob("*")):
+        if f.suffix in (".hip", ".h"):
+            h.update(f.name.encode())
+            h.update(f.read_bytes())
+    return h.hexdigest()
+
+
+def recorded_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from profiles/hbm_traffic.json (rocprofv3 --pmc
+    FETCH_SIZE / WRITE_SIZE, scaled by the same counters' reading for a plain copy), or None when
+    the kernels changed since the counters were taken."""
+    f = ROOT / "profiles" / "hbm_traffic.json"
+    if not f.exists():
+        return None
+    rec = json.loads(f.read_text())
+    if rec.get("source_sha256") != kernel_source_hash():
+        return None
+    w = rec.get("workloads", {}).get(workload_name)
+    return None if w is None else w.get("traffic_bytes")
+
+
+def calibrate_copy():
+    import torch
+    n = 1 << 30
+    src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(5):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps({"calibrate_copy_bytes": n, "reads": n, "writes": n, "launches": 5}))
+
+
 def main():
     args = parse_args()
+    if args.calibrate_copy:
+        calibrate_copy()
+        return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the head shards by vocabulary or by rows "
               "without changing the per-GPU kernel); use --gpus 1", file=sys.stderr)
@@ -214,6 +257,7 @@ def main():
     t = runner.time_steps(head, st, args.steps, args.warmup)
     torch.cuda.synchronize()
     head_rep = report(head, st, t)
+    head_rep["roofline"]["traffic"] = recorded_traffic(head["name"])
     cpu = None if args.no_cpu else cpu_baseline(runner, head, st)
     del st
     sweep = []
@@ -236,7 +280,7 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16 inputs, fp32 accumulate",
+        "dtype": "bf16",
         "data": "synthetic (seeded N(0,0.02) W, N(0,1) h, Zipf(1.1)-ranked subsets); cold: rotating W_sub copies > 1 GiB",
         "config": {"workload": "%s: rows=%d H=%d V_draft=%d k=%d (untrimmed baseline head, identity d2t)"
                                % (head["name"], head["rows"], head["H"], head["Vd"], head["k"]),
