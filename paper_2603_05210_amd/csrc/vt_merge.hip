@@ -32,34 +32,91 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
     const int lane = tid & 63;
     const int wave = tid >> 6;
 
+    // Pass A over the P partial statistics only (8 bytes each): softmax partials, and a bound
+    // below which no candidate can be among the row's k best.  Split the lists into 16 classes
+    // (list index mod 16); `bound` = the smallest of the 16 class maxima of the lists' best
+    // logits.  16 >= KP distinct candidates are >= bound, so a list whose best logit is strictly
+    // below it cannot contribute and its entries are never read.
+    __shared__ float sm_cls[NW][16];
+    constexpr int CH = 8;  // statistics fetched per thread and batch (independent loads in flight together)
+    float m = neg_inf(), s = 0.0f;
+    float cls = neg_inf();  // this thread's lists all fall in class tid % 16 (stride 256)
+    float best0[CH];        // best logits of the first batch, kept for pass B
+#pragma unroll
+    for (int c = 0; c < CH; ++c)
+        best0[c] = neg_inf();
+    for (int base = 0; base < P; base += CH * kMergeThreads) {
+        float2 st[CH];
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int p = base + c * kMergeThreads + tid;
+            st[c] = (p < P) ? part_stat[(size_t)r * P + p] : make_float2(neg_inf(), 0.0f);
+        }
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            stat_merge(m, s, st[c].x, st[c].y);
+            cls = fmaxf(cls, st[c].x);
+            if (base == 0)
+                best0[c] = st[c].x;
+        }
+    }
+    float bound = neg_inf();
+    if (KP <= 16 && P >= 64) {
+        // class maxima: over the four 16-lane rows of a wave, then over the waves
+        {
+            const auto r16 = __builtin_amdgcn_permlane16_swap(__float_as_int(cls), __float_as_int(cls), false, false);
+            cls = fmaxf(__int_as_float(r16[0]), __int_as_float(r16[1]));
+            const auto r32 = __builtin_amdgcn_permlane32_swap(__float_as_int(cls), __float_as_int(cls), false, false);
+            cls = fmaxf(__int_as_float(r32[0]), __int_as_float(r32[1]));
+        }
+        if (lane < 16)
+            sm_cls[wave][lane] = cls;
+        __syncthreads();
+        float c = sm_cls[0][lane & 15];
+#pragma unroll
+        for (int w = 1; w < NW; ++w)
+            c = fmaxf(c, sm_cls[w][lane & 15]);
+        bound = -row16_max(-c);  // min over the 16 classes
+    }
+
     TopList<KP> L;
     L.clear();
-    float m = neg_inf(), s = 0.0f;
-    for (int p = tid; p < P; p += kMergeThreads) {
+    bool first = true;
+    auto take_list = [&](int p) {
         const size_t slot = (size_t)r * P + p;
-        const float2 st = part_stat[slot];
-        stat_merge(m, s, st.x, st.y);
         const float* pv = part_val + slot * KP;
         const int32_t* pi = part_idx + slot * KP;
-        if (p == tid) {  // the first list of a thread is taken as it is (partial lists are sorted)
+        float lv[KP];
+        int li[KP];
+#pragma unroll
+        for (int q = 0; q < KP; ++q) {
+            lv[q] = pv[q];
+            li[q] = pi[q];
+        }
+        if (first) {  // the first list a thread keeps is taken as it is (partial lists are sorted)
 #pragma unroll
             for (int q = 0; q < KP; ++q) {
-                L.v[q] = pv[q];
-                L.i[q] = pi[q];
+                L.v[q] = lv[q];
+                L.i[q] = li[q];
             }
-        } else if (!(st.x < L.v[KP - 1])) {  // st.x is the list's best logit: skip lists that cannot enter
-            float lv[KP];
-            int li[KP];
-#pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                lv[q] = pv[q];
-                li[q] = pi[q];
-            }
+            first = false;
+        } else {
 #pragma unroll
             for (int q = 0; q < KP; ++q)
                 if (better(lv[q], li[q], L.v[KP - 1], L.i[KP - 1]))
                     L.insert(lv[q], li[q]);
         }
+    };
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+        const int p = c * kMergeThreads + tid;
+        if (p < P && !(best0[c] < bound) && !(best0[c] < L.v[KP - 1]))
+            take_list(p);
+    }
+    for (int p = CH * kMergeThreads + tid; p < P; p += kMergeThreads) {  // beyond the first batch (very large P)
+        const float best = part_stat[(size_t)r * P + p].x;
+        if (!(best < bound) && !(best < L.v[KP - 1]))
+            take_list(p);
     }
 
     wave_stat_merge(m, s, true);
