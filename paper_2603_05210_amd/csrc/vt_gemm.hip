@@ -26,12 +26,14 @@ namespace vt {
 // tile 0: 128 tokens x 128 rows, 4 waves (2x2), 64x64 per wave.
 // tile 1: 256 tokens x 256 rows, 4 waves (2x2), 128x128 per wave, two LDS stages, one workgroup per CU.
 // tile 3: 256 tokens x 256 rows, 4 waves, 128x128 per wave, operands by LDS-DMA into four 32-deep stages.
+// tile 6: as tile 5 but operands by LDS-DMA into four 32-deep stages.
+// tile 5: 256 tokens x 256 rows, 8 waves (2x4), 128x64 per wave, two LDS stages, one workgroup per CU.
 // tile 4: 256 tokens x 128 rows, 4 waves, 128x64 per wave, LDS-DMA into three stages, two workgroups per CU.
 // tile 2: 256 tokens x 128 rows, 4 waves (2x2), 128x64 per wave, one LDS stage, two workgroups per CU.
 struct TileInfo {
     int BMV, BNR, parts_per_vtile;
 };
-static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}, {256, 128, 4}, {256, 256, 4}, {256, 128, 4}};
+static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}, {256, 128, 4}, {256, 256, 4}, {256, 128, 4}, {256, 256, 4}, {256, 256, 4}};
 
 void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 {
@@ -44,7 +46,7 @@ int gemm_pick_tile(int rows, int H, int Vd, int KP)
 {
     (void)Vd;
     if (const char* e = getenv("VT_GEMM_TILE"))  // exploration override
-        if (e[0] >= '0' && e[0] <= '4' && (e[0] == '0' || (KP <= 16 && (H % 64) == 0)))
+        if (e[0] >= '0' && e[0] <= '6' && (e[0] == '0' || (KP <= 16 && (H % 64) == 0)))
             return e[0] - '0';
     // the large tiles have no K-tail variant and no room for long candidate lists
     if (KP > 16 || rows <= 128 || (H % 64) != 0)

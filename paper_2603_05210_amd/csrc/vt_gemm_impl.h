@@ -403,7 +403,7 @@ __global__ void __launch_bounds__(WV* WR * 64, ONE_STAGE ? 2 : 1) gemm_head_kern
         }
     }
 
-    head_epilogue<WV, WR, SV, SR, KP, !ONE_STAGE>(acc, a, smem, v0, r0, vt_i, wave, lane);
+    head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
 }
 
 // ---- LDS-DMA variant of the projection kernel ----
@@ -593,7 +593,7 @@ __global__ void __launch_bounds__(WV* WR * 64, MINB) gemm_head_dma_kernel(GemmAr
         });
         k_tile(kt, F{}, std::integral_constant<int, 0>{}, F{});
     }
-    head_epilogue<WV, WR, SV, SR, KP, (MINB == 1)>(acc, a, smem, v0, r0, vt_i, wave, lane);
+    head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
 }
 
 template <int WV, int WR, int SV, int SR, int KP, int NSTG, int MINB>
@@ -602,7 +602,7 @@ static hipError_t launch_tile_dma(const Plan& p, const GemmArgs& ga, hipStream_t
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
     constexpr size_t lds_loop = (size_t)NSTG * (BMV + BNR) * 64;  // stages of 64-byte rows
     constexpr size_t lds_epi =
-        (size_t)(NT / 64) * ((MINB == 1 ? (size_t)SV * 16 * 64 * 4 : 0) + (size_t)KP * 64 * 8);
+        (size_t)(NT / 64) * ((SV * SR > 8 ? (size_t)SV * 16 * 64 * 4 : 0) + (size_t)KP * 64 * 8);
     constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
     if ((p.H % 32) != 0)
@@ -626,7 +626,7 @@ static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
     constexpr size_t lds_loop = (size_t)(ONE_STAGE ? 1 : 2) * (BMV + BNR) * 128;  // operand stage(s)
     constexpr size_t lds_epi =
-        (size_t)(NT / 64) * ((ONE_STAGE ? 0 : (size_t)SV * 16 * 64 * 4) + (size_t)KP * 64 * 8);  // epilogue columns
+        (size_t)(NT / 64) * ((SV * SR > 8 ? (size_t)SV * 16 * 64 * 4 : 0) + (size_t)KP * 64 * 8);  // epilogue columns
     constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
     const bool guard = (p.H % 64) != 0;
@@ -660,10 +660,14 @@ static hipError_t launch_gemm_kp(const Plan& p, const GemmArgs& ga, hipStream_t 
             return launch_tile<2, 2, 4, 4, KP, false, false>(p, ga, s);
         if (p.tile == 2)
             return launch_tile<2, 2, 4, 2, KP, false, true>(p, ga, s);
+        if (p.tile == 5)
+            return launch_tile<2, 4, 4, 2, KP, false, false>(p, ga, s);
         if (p.tile == 3)
             return launch_tile_dma<2, 2, 4, 4, KP, 4, 1>(p, ga, s);
         if (p.tile == 4)
             return launch_tile_dma<2, 2, 4, 2, KP, 3, 2>(p, ga, s);
+        if (p.tile == 6)
+            return launch_tile_dma<2, 4, 4, 2, KP, 4, 1>(p, ga, s);
     }
     return hipErrorInvalidValue;
 }
