@@ -16,24 +16,19 @@
 // 128 B with the piece index XOR-swizzled by (row/2)%8 so that the 16-byte fragment reads of
 // 32 different rows spread over all banks.  Two LDS stages; the next stage's global loads
 // are issued before the current stage's MFMAs.
-#include <cstdlib>
-
 #include "vt_internal.h"
 
 namespace vt {
 
 // ---- tile shapes ----
-// tile 0: 128 tokens x 128 rows, 4 waves (2x2), 64x64 per wave.
-// tile 1: 256 tokens x 256 rows, 4 waves (2x2), 128x128 per wave, two LDS stages, one workgroup per CU.
-// tile 3: 256 tokens x 256 rows, 4 waves, 128x128 per wave, operands by LDS-DMA into four 32-deep stages.
-// tile 6: as tile 5 but operands by LDS-DMA into four 32-deep stages.
-// tile 5: 256 tokens x 256 rows, 8 waves (2x4), 128x64 per wave, two LDS stages, one workgroup per CU.
-// tile 4: 256 tokens x 128 rows, 4 waves, 128x64 per wave, LDS-DMA into three stages, two workgroups per CU.
-// tile 2: 256 tokens x 128 rows, 4 waves (2x2), 128x64 per wave, one LDS stage, two workgroups per CU.
+// tile 0: 128 tokens x 128 rows, 4 waves (2x2), 64x64 per wave: any k <= 64, any H % 8 == 0.
+// tile 1: 256 tokens x 256 rows, 8 waves (2x4), 128x64 per wave (128 accumulators, two waves per
+//         SIMD hide each other's LDS / barrier / epilogue stalls; operand traffic from L2 is that
+//         of the largest tile): k <= 16, H % 64 == 0.
 struct TileInfo {
     int BMV, BNR, parts_per_vtile;
 };
-static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}, {256, 128, 4}, {256, 256, 4}, {256, 128, 4}, {256, 256, 4}, {256, 256, 4}};
+static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}};
 
 void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 {
@@ -45,15 +40,10 @@ void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 int gemm_pick_tile(int rows, int H, int Vd, int KP)
 {
     (void)Vd;
-    if (const char* e = getenv("VT_GEMM_TILE"))  // exploration override
-        if (e[0] >= '0' && e[0] <= '6' && (e[0] == '0' || (KP <= 16 && (H % 64) == 0)))
-            return e[0] - '0';
-    // the large tiles have no K-tail variant and no room for long candidate lists
+    // the large tile has no K-tail variant and no room for long candidate lists
     if (KP > 16 || rows <= 128 || (H % 64) != 0)
         return 0;
-    // 256x128 with two workgroups per CU measured fastest on the tree-drafting shapes: the VALU
-    // epilogue of one workgroup overlaps the MFMA loop of the other
-    return 2;
+    return 1;
 }
 
 hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s)

@@ -184,12 +184,8 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
     });
 }
 
-// ONE_STAGE = false: two LDS stages of the operand tiles, one workgroup per CU (large tiles).
-// ONE_STAGE = true:  a single LDS stage (half the LDS, <= 256 registers per lane) so that TWO
-//                    workgroups share a CU: while one waits at its barriers or runs its VALU
-//                    epilogue, the other keeps the matrix cores busy.
-template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K, bool ONE_STAGE>
-__global__ void __launch_bounds__(WV* WR * 64, ONE_STAGE ? 2 : 1) gemm_head_kernel(GemmArgs a)
+template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K>
+__global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
 {
     constexpr int BMV = WV * SV * 32;    // draft tokens per workgroup tile
     constexpr int BNR = WR * SR * 32;    // hidden-state rows per workgroup tile
@@ -324,7 +320,7 @@ __global__ void __launch_bounds__(WV* WR * 64, ONE_STAGE ? 2 : 1) gemm_head_kern
     // piece i of tile kt+2, so every load has a whole K tile of MFMAs to arrive and neither the
     // texture path nor the LDS sees a burst.  sched_barrier pins the order; the compiler still
     // places the s_waitcnt.
-    constexpr int TSTEPS = ONE_STAGE ? 4 : 3;           // K-steps that carry staging turnover
+    constexpr int TSTEPS = 3;                           // K-steps that carry staging turnover
     constexpr int NPAIR = (NLD + TSTEPS - 1) / TSTEPS;  // staging pieces turned over per such K-step
     auto k_step = [&](auto SET, auto KS, auto KSN, const u32x4* __restrict__ rd_next, auto DO_READ,
                       u32x4* __restrict__ wr, auto DO_WRITE, int kt_load, auto DO_LOAD) {
@@ -370,13 +366,13 @@ __global__ void __launch_bounds__(WV* WR * 64, ONE_STAGE ? 2 : 1) gemm_head_kern
         k_step(C1{}, C3{}, C0{}, smem + ((kt & 1) ^ 1) * STAGE, HAS1, wr, std::false_type{}, 0, std::false_type{});
     };
 
-    if constexpr (!ONE_STAGE) {
-        load_stage(0);
-        store_stage(smem);
-        if (KT > 1)
-            load_stage(1);
-        __syncthreads();
-        read_frags(smem, C0{}, C0{});
+    load_stage(0);
+    store_stage(smem);
+    if (KT > 1)
+        load_stage(1);
+    __syncthreads();
+    read_frags(smem, C0{}, C0{});
+    {
         int kt = 0;
         for (; kt + 2 < KT; ++kt)
             k_tile(kt, std::true_type{}, std::true_type{});
@@ -385,255 +381,25 @@ __global__ void __launch_bounds__(WV* WR * 64, ONE_STAGE ? 2 : 1) gemm_head_kern
             ++kt;
         }
         k_tile(kt, std::false_type{}, std::false_type{});
-    } else {
-        // Single LDS stage: barrier, write the tile held in the staging registers, request the
-        // next tile, barrier, then the four K-steps with register-double-buffered fragments.
-        load_stage(0);
-        for (int kt = 0; kt < KT; ++kt) {
-            __syncthreads();  // every wave has finished reading the previous tile
-            store_stage(smem);
-            if (kt + 1 < KT)
-                load_stage(kt + 1);
-            __syncthreads();  // the tile is complete in LDS
-            read_frags(smem, C0{}, C0{});
-            k_step(C0{}, C0{}, C1{}, smem, std::true_type{}, smem, std::false_type{}, 0, std::false_type{});
-            k_step(C1{}, C1{}, C2{}, smem, std::true_type{}, smem, std::false_type{}, 0, std::false_type{});
-            k_step(C0{}, C2{}, C3{}, smem, std::true_type{}, smem, std::false_type{}, 0, std::false_type{});
-            k_step(C1{}, C3{}, C0{}, smem, std::false_type{}, smem, std::false_type{}, 0, std::false_type{});
-        }
     }
 
     head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
 }
 
-// ---- LDS-DMA variant of the projection kernel ----
-// Operand tiles go from memory straight into LDS (global_load_lds_dwordx4): no staging
-// registers, no ds_write instructions, and the prefetch depth is only limited by LDS capacity.
-// BK = 32 (two K-steps of 16 per tile, tile row = 64 B = four 16-byte pieces), NSTG = 4 stages:
-// while tile kt is multiplied, tile kt+1 is resident and tiles kt+2, kt+3 are in flight.
-// One DMA instruction of a wave fills 16 consecutive tile rows (lane l -> row l/4, piece l%4);
-// the XOR swizzle of the LDS layout (piece ^ (row/4)%4, conflict-free for the 16-byte fragment
-// reads) is applied on the global side by choosing which piece each lane fetches.
-// DMA completion is tracked by hand: s_waitcnt vmcnt(n) before the single barrier of a K tile
-// (a raw s_barrier: the fence inside __syncthreads would wait for every outstanding DMA).
-template <int N>
-__device__ __forceinline__ void wait_vm_lgkm0()
-{
-    // vmcnt(N) lgkmcnt(0); expcnt untouched
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
-}
-__device__ __forceinline__ void raw_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
-
-template <int WV, int WR, int SV, int SR, int KP, int NSTG, int MINB>
-__global__ void __launch_bounds__(WV* WR * 64, MINB) gemm_head_dma_kernel(GemmArgs a)
-{
-    constexpr int BMV = WV * SV * 32;
-    constexpr int BNR = WR * SR * 32;
-    constexpr int NT = WV * WR * 64;
-    constexpr int NW = NT / 64;
-    constexpr int TROWS = BMV + BNR;
-    constexpr int DEPTH = NSTG - 1;             // tile kt+DEPTH is requested while tile kt is multiplied
-    constexpr int STAGE = TROWS * 4;            // 16-byte pieces per stage
-    constexpr int NDMA = TROWS / 16 / NW;       // DMA instructions per wave per K tile
-    constexpr int NMF = SV * SR;                // MFMAs per K-step
-    constexpr int NFR = SV + SR;                // fragment reads per K-step
-    static_assert(TROWS % (16 * NW) == 0 && BMV % 16 == 0, "DMA instructions must tile the stage evenly");
-    static_assert(NFR <= NMF && NDMA <= NMF, "a K-step must have room for its memory operations");
-    static_assert((DEPTH - 1) * NDMA <= 63 && DEPTH >= 1, "outstanding DMA count must fit vmcnt");
-    extern __shared__ u32x4 smem[];
-    typedef __attribute__((address_space(3))) void* lds_ptr;
-
-    const int total = a.n_vtiles * a.n_rtiles;
-    const int per_xcd = (total + 7) >> 3;
-    const int lin = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if ((int)(blockIdx.x >> 3) >= per_xcd || lin >= total)
-        return;
-    const int vt_i = lin / a.n_rtiles;
-    const int rt_i = lin - vt_i * a.n_rtiles;
-    const int v0 = vt_i * BMV;
-    const int r0 = rt_i * BNR;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wv = wave / WR;
-    const int wr = wave - wv * WR;
-    const int nchunk = a.nchunk;
-    const size_t row_bytes = (size_t)nchunk * 16;
-    const char* w_base = static_cast<const char*>(a.W) + (size_t)v0 * row_bytes;
-    const char* h_base = static_cast<const char*>(a.h) + (size_t)r0 * row_bytes;
-
-    // global side of the DMA: which (row, piece) this lane fetches in instruction i
-    const int dpiece = (lane & 3) ^ ((lane >> 4) & 3);
-    uint32_t goff[NDMA];
-    static_for<NDMA>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        const int rowid = (i * NW + wave) * 16 + (lane >> 2);
-        if (rowid < BMV) {
-            int v = v0 + rowid;
-            v = (v < a.Vd ? v : a.Vd - 1) - v0;
-            goff[i] = (uint32_t)v * (uint32_t)row_bytes + dpiece * 16;
-        } else {
-            int r = r0 + rowid - BMV;
-            r = (r < a.rows ? r : a.rows - 1) - r0;
-            goff[i] = (uint32_t)r * (uint32_t)row_bytes + dpiece * 16;
-        }
-    });
-    auto dma_one = [&](int kt, auto I) {
-        constexpr int i = decltype(I)::value;
-        const bool is_w = ((i * NW + wave) * 16) < BMV;  // uniform per wave and instruction
-        const char* src = (is_w ? w_base : h_base) + (size_t)kt * 64 + goff[i];
-        u32x4* dst = smem + (kt % NSTG) * STAGE + (i * NW + wave) * 64;
-        __builtin_amdgcn_global_load_lds(reinterpret_cast<const u32x4*>(src), (lds_ptr)dst, 16, 0, 0);
-    };
-    auto dma_tile = [&](int kt) { static_for<NDMA>([&](auto I) { dma_one(kt, I); }); };
-
-    // fragment addressing (row = 4 pieces)
-    const int frow = lane & 31;
-    const int fhalf = lane >> 5;
-    const int fsw = (frow >> 2) & 3;
-    const int a_base = (wv * SV * 32 + frow) * 4;
-    const int b_base = (BMV + wr * SR * 32 + frow) * 4;
-
-    f32x16 acc[SV * SR];
-    static_for<SV * SR>([&](auto I) {
-        constexpr int i = decltype(I)::value;
-        static_for<16>([&](auto E) { acc[i][decltype(E)::value] = 0.0f; });
-    });
-    bf16x8 af[2][SV], bfr[2][SR];
-    auto read_one = [&](const u32x4* rd, auto KS, auto SET, auto F) {
-        constexpr int ks = decltype(KS)::value;
-        constexpr int set = decltype(SET)::value;
-        constexpr int f = decltype(F)::value;
-        const int pc = ((ks * 2 + fhalf) ^ fsw);
-        if constexpr (f < SV)
-            af[set][f] = __builtin_bit_cast(bf16x8, rd[a_base + f * 32 * 4 + pc]);
-        else
-            bfr[set][f - SV] = __builtin_bit_cast(bf16x8, rd[b_base + (f - SV) * 32 * 4 + pc]);
-    };
-    auto mfma_one = [&](auto SET, auto M) {
-        constexpr int set = decltype(SET)::value;
-        constexpr int sv = decltype(M)::value / SR;
-        constexpr int sr = decltype(M)::value % SR;
-        acc[sv * SR + sr] =
-            __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][sv], bfr[set][sr], acc[sv * SR + sr], 0, 0, 0);
-    };
-    using C0 = std::integral_constant<int, 0>;
-    using C1 = std::integral_constant<int, 1>;
-
-    // One K tile.  HAS_DMA: tile kt+DEPTH exists and is requested now.  NOUT: how many younger tiles
-    // may still be in flight when tile kt+1 must be complete.  HAS_NEXT: tile kt+1 exists.
-    auto k_tile = [&](int kt, auto HAS_DMA, auto NOUT, auto HAS_NEXT) {
-        constexpr bool has_dma = decltype(HAS_DMA)::value;
-        constexpr int nout = decltype(NOUT)::value;
-        constexpr bool has_next = decltype(HAS_NEXT)::value;
-        const u32x4* rd = smem + (kt % NSTG) * STAGE;
-        const u32x4* rdn = smem + ((kt + 1) % NSTG) * STAGE;
-        // K-step 0: fragments of K-step 1 and the DMA of tile kt+DEPTH ride along
-        static_for<NMF>([&](auto M) {
-            constexpr int m = decltype(M)::value;
-            mfma_one(C0{}, M);
-            if constexpr (m < NFR)
-                read_one(rd, C1{}, C1{}, M);
-            if constexpr (has_dma && m >= NMF - NDMA)
-                dma_one(kt + DEPTH, std::integral_constant<int, m - (NMF - NDMA)>{});
-            __builtin_amdgcn_sched_barrier(0);
-        });
-        // tile kt+1 complete (own DMA), own LDS reads returned; then everybody's
-        if constexpr (has_next) {
-            wait_vm_lgkm0<nout * NDMA>();
-            raw_barrier();
-        }
-        // K-step 1: first fragments of tile kt+1 ride along
-        static_for<NMF>([&](auto M) {
-            constexpr int m = decltype(M)::value;
-            mfma_one(C1{}, M);
-            if constexpr (has_next && m < NFR)
-                read_one(rdn, C0{}, C0{}, M);
-            __builtin_amdgcn_sched_barrier(0);
-        });
-    };
-
-    const int KT = nchunk >> 2;  // H is a multiple of 32 here
-    // prologue: request tiles 0..DEPTH-1, wait for tile 0
-    static_for<DEPTH>([&](auto D) {
-        if (decltype(D)::value < KT)
-            dma_tile(decltype(D)::value);
-    });
-    {
-        bool done = false;
-        static_for<DEPTH>([&](auto D) {  // D younger tiles may stay in flight: the largest D with D+1 <= min(KT, DEPTH)
-            constexpr int younger = DEPTH - 1 - decltype(D)::value;
-            if (!done && younger + 1 <= KT) {
-                wait_vm_lgkm0<younger * NDMA>();
-                done = true;
-            }
-        });
-    }
-    raw_barrier();
-    static_for<NFR>([&](auto F) { read_one(smem, C0{}, C0{}, F); });
-    {
-        using T = std::true_type;
-        using F = std::false_type;
-        int kt = 0;
-        for (; kt + DEPTH < KT; ++kt)  // steady state: DEPTH-1 younger tiles in flight at the barrier
-            k_tile(kt, T{}, std::integral_constant<int, DEPTH - 1>{}, T{});
-        // drain: no more requests; fewer and fewer tiles in flight
-        static_for<DEPTH - 1>([&](auto D) {
-            constexpr int younger = DEPTH - 2 - decltype(D)::value;  // DEPTH-2 .. 0
-            if (kt + younger + 1 < KT) {
-                k_tile(kt, F{}, std::integral_constant<int, younger>{}, T{});
-                ++kt;
-            }
-        });
-        k_tile(kt, F{}, std::integral_constant<int, 0>{}, F{});
-    }
-    head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
-}
-
-template <int WV, int WR, int SV, int SR, int KP, int NSTG, int MINB>
-static hipError_t launch_tile_dma(const Plan& p, const GemmArgs& ga, hipStream_t s)
-{
-    constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
-    constexpr size_t lds_loop = (size_t)NSTG * (BMV + BNR) * 64;  // stages of 64-byte rows
-    constexpr size_t lds_epi =
-        (size_t)(NT / 64) * ((SV * SR > 8 ? (size_t)SV * 16 * 64 * 4 : 0) + (size_t)KP * 64 * 8);
-    constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
-    static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
-    if ((p.H % 32) != 0)
-        return hipErrorInvalidValue;
-    void (*kern)(GemmArgs) = gemm_head_dma_kernel<WV, WR, SV, SR, KP, NSTG, MINB>;
-    static bool lds_raised = false;
-    if (lds > 48 * 1024 && !lds_raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess)
-            return e;
-        lds_raised = true;
-    }
-    hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(NT), lds, s, ga);
-    return hipGetLastError();
-}
-
-template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD, bool ONE_STAGE>
+template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD>
 static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
 {
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
-    constexpr size_t lds_loop = (size_t)(ONE_STAGE ? 1 : 2) * (BMV + BNR) * 128;  // operand stage(s)
+    constexpr size_t lds_loop = (size_t)2 * (BMV + BNR) * 128;  // two operand stages
     constexpr size_t lds_epi =
         (size_t)(NT / 64) * ((SV * SR > 8 ? (size_t)SV * 16 * 64 * 4 : 0) + (size_t)KP * 64 * 8);  // epilogue columns
     constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
     const bool guard = (p.H % 64) != 0;
-    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false, ONE_STAGE>;
+    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false>;
     if constexpr (ALLOW_GUARD) {
         if (guard)
-            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true, ONE_STAGE>;
+            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true>;
     } else {
         if (guard)
             return hipErrorInvalidValue;
@@ -654,20 +420,10 @@ template <int KP>
 static hipError_t launch_gemm_kp(const Plan& p, const GemmArgs& ga, hipStream_t s)
 {
     if (p.tile == 0)
-        return launch_tile<2, 2, 2, 2, KP, true, false>(p, ga, s);
+        return launch_tile<2, 2, 2, 2, KP, true>(p, ga, s);
     if constexpr (KP <= 16) {
         if (p.tile == 1)
-            return launch_tile<2, 2, 4, 4, KP, false, false>(p, ga, s);
-        if (p.tile == 2)
-            return launch_tile<2, 2, 4, 2, KP, false, true>(p, ga, s);
-        if (p.tile == 5)
-            return launch_tile<2, 4, 4, 2, KP, false, false>(p, ga, s);
-        if (p.tile == 3)
-            return launch_tile_dma<2, 2, 4, 4, KP, 4, 1>(p, ga, s);
-        if (p.tile == 4)
-            return launch_tile_dma<2, 2, 4, 2, KP, 3, 2>(p, ga, s);
-        if (p.tile == 6)
-            return launch_tile_dma<2, 4, 4, 2, KP, 4, 1>(p, ga, s);
+            return launch_tile<2, 4, 4, 2, KP, false>(p, ga, s);
     }
     return hipErrorInvalidValue;
 }

@@ -86,25 +86,22 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         const size_t slot = (size_t)r * P + p;
         const float* pv = part_val + slot * KP;
         const int32_t* pi = part_idx + slot * KP;
-        float lv[KP];
-        int li[KP];
-#pragma unroll
-        for (int q = 0; q < KP; ++q) {
-            lv[q] = pv[q];
-            li[q] = pi[q];
-        }
         if (first) {  // the first list a thread keeps is taken as it is (partial lists are sorted)
 #pragma unroll
             for (int q = 0; q < KP; ++q) {
-                L.v[q] = lv[q];
-                L.i[q] = li[q];
+                L.v[q] = pv[q];
+                L.i[q] = pi[q];
             }
             first = false;
-        } else {
-#pragma unroll
-            for (int q = 0; q < KP; ++q)
-                if (better(lv[q], li[q], L.v[KP - 1], L.i[KP - 1]))
-                    L.insert(lv[q], li[q]);
+        } else {  // later lists: sorted, so stop at the first entry that cannot enter
+#pragma unroll 1
+            for (int q = 0; q < KP; ++q) {
+                const float x = pv[q];
+                const int ix = pi[q];
+                if (!better(x, ix, L.v[KP - 1], L.i[KP - 1]))
+                    break;
+                L.insert(x, ix);
+            }
         }
     };
 #pragma unroll
