@@ -33,7 +33,7 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
     bool streaming = rows <= kGemvMaxRows;
     if (streaming) {
         p.NR = next_pow2((int)rows);
-        p.J = p.NR >= 16 ? 2 : 4;
+        p.J = p.NR == 1 ? 1 : 2;
         int rpb = (int)((Vd + kGemvTargetBlocks - 1) / kGemvTargetBlocks);
         rpb = (rpb + 7) / 8 * 8;
         if (rpb > kGemvMaxRowsPerBlock)

@@ -169,15 +169,6 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
     const int nchunk = a.nchunk;
     float* zbuf = reinterpret_cast<float*>(smem + NR * nchunk);  // [NR][rpb]
 
-    // hidden states -> LDS (rows beyond `rows` repeat the last one; their results are dropped)
-    for (int x = tid; x < NR * nchunk; x += kGemvThreads) {
-        const int r = x / nchunk;
-        const int c = x - r * nchunk;
-        const int rr = r < a.rows ? r : a.rows - 1;
-        smem[x] = a.h[(size_t)rr * nchunk + c];
-    }
-    __syncthreads();
-
     const int p_l = (NP > 1) ? (lane >> (6 - ilog2(NP))) : 0;  // pair this lane ends up with
     const int r_l = p_l / J;
     const int jj_l = p_l - r_l * J;
@@ -249,7 +240,16 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
     };
     u32x4 bufA[J], bufB[J];
     if (g < ngroups)
-        load_pos(g, 0, bufA);
+        load_pos(g, 0, bufA);  // the first W_sub loads are in flight while the hidden states are staged
+
+    // hidden states -> LDS (rows beyond `rows` repeat the last one; their results are dropped)
+    for (int x = tid; x < NR * nchunk; x += kGemvThreads) {
+        const int r = x / nchunk;
+        const int c = x - r * nchunk;
+        const int rr = r < a.rows ? r : a.rows - 1;
+        smem[x] = a.h[(size_t)rr * nchunk + c];
+    }
+    __syncthreads();
     while (g < ngroups) {
         step(bufA, bufB);
         if (g >= ngroups)
@@ -386,11 +386,12 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.out_ids = a.out_ids;
     ga.out_logp = a.out_logp;
     ga.lse_out = a.lse_out;
+    // rows of W_sub a wave reduces together (J): measured best 1 for a single hidden row, 2 otherwise
     switch (p.NR) {
-    case 1: return launch_one<1, 4, true>(p, ga, s);
-    case 2: return launch_one<2, 4, true>(p, ga, s);
-    case 4: return launch_one<4, 4, true>(p, ga, s);
-    case 8: return launch_one<8, 4, true>(p, ga, s);
+    case 1: return launch_one<1, 1, true>(p, ga, s);
+    case 2: return launch_one<2, 2, true>(p, ga, s);
+    case 4: return launch_one<4, 2, true>(p, ga, s);
+    case 8: return launch_one<8, 2, true>(p, ga, s);
     case 16: return launch_one<16, 2, true>(p, ga, s);
     }
     return hipErrorInvalidValue;
