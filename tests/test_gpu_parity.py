@@ -67,7 +67,21 @@ SMALL = [
 ]
 
 
-@pytest.mark.parametrize("rows,H,V,Vd,k", SMALL)
+EDGE = [
+    # rows, H, V, Vd, k           degenerate and limit shapes
+    (1, 8, 10, 1, 1),             # one draft token, minimum H
+    (1, 8, 40, 5, 5),             # k == V_draft
+    (20, 8, 40, 5, 5),            # the same through the MFMA regime
+    (16, 72, 900, 600, 64),       # 16 rows, longest list, H not a multiple of 64
+    (17, 72, 900, 600, 64),       # first row count of the MFMA regime, longest list, K tail
+    (2, 64, 150000, 140000, 10),  # more workgroup partials than the fused merge takes
+    (9, 128, 150000, 133000, 3),
+    (129, 64, 700, 257, 16),      # one row and one token past a tile edge
+    (256, 128, 2000, 512, 16),    # exact tile multiples
+]
+
+
+@pytest.mark.parametrize("rows,H,V,Vd,k", SMALL + EDGE)
 def test_small_cases_full_comparison(rows, H, V, Vd, k):
     _say("case rows=%d H=%d V=%d Vd=%d k=%d" % (rows, H, V, Vd, k))
     seed = rows * 1000 + k
@@ -175,6 +189,39 @@ def test_results_do_not_depend_on_run(capsys):
         b = run_gpu(h, W_dev, d2t_dev, k)
         assert np.array_equal(a[0], b[0]) and np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
         assert np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
+
+
+@pytest.mark.parametrize("rows,H,Vd,k", [(1, 1024, 30011, 10), (6, 512, 9001, 4), (300, 512, 3000, 8)])
+def test_hip_graph_replays_match_eager(rows, H, Vd, k):
+    """A captured draft step replays correctly (several replays, eager work in between): the
+    step allocates nothing, takes no host round trip and its fused merge re-arms itself."""
+    W = synth.gen_W(31, Vd, H, std=0.05)
+    W_dev = to_dev_bf16(W)
+    d2t_dev = torch.arange(Vd, dtype=torch.int32, device=DEV)
+    hs = [to_dev_bf16(synth.gen_h(40 + i, rows, H)) for i in range(3)]
+    h_in = hs[0].clone()
+    ws = torch.empty(vt.vt_draft_head_workspace_bytes(rows, H, Vd, k), dtype=torch.uint8, device=DEV)
+    ids = torch.empty((rows, k), dtype=torch.int32, device=DEV)
+    lp = torch.empty((rows, k), dtype=torch.float32, device=DEV)
+    eager = []
+    for h in hs:
+        a, b = vt.vt_draft_head(h, W_dev, d2t_dev, k)
+        torch.cuda.synchronize()
+        eager.append((a.cpu().numpy(), b.cpu().numpy()))
+    vt.vt_draft_head(h_in, W_dev, d2t_dev, k, ids, lp, ws)  # warm: one-time kernel attributes are set
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        vt.vt_draft_head(h_in, W_dev, d2t_dev, k, ids, lp, ws)
+    for rep in range(6):
+        i = rep % 3
+        h_in.copy_(hs[i])
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(ids.cpu().numpy(), eager[i][0]), "replay %d" % rep
+        assert np.array_equal(lp.cpu().numpy().view(np.uint32), eager[i][1].view(np.uint32)), "replay %d" % rep
+        junk = torch.randn(1000, device=DEV).sum().item()  # unrelated eager work between replays
+        assert junk == junk
 
 
 # ------------------------------------------------------------------ full-size workloads
