@@ -186,36 +186,32 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
+__device__ __forceinline__ int wave_min_i(int x)
+{
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xf, 0xf, false));
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        x = min((int)r[0], (int)r[1]);
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        x = min((int)r[0], (int)r[1]);
+    }
+    return x;
+}
+
 // Best (logit, index) pair over the wave under the strict order; every lane returns it.
+// Two cheap reductions instead of one over pairs: the largest logit, then the smallest index
+// among the lanes that hold it.
 __device__ __forceinline__ void wave_best(float& v, int& i)
 {
-#define VT_BEST_DPP(CTRL)                                                                                  \
-    {                                                                                                      \
-        const float ov = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false)); \
-        const int oi = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);                           \
-        const bool c = better(ov, oi, v, i);                                                               \
-        v = c ? ov : v;                                                                                    \
-        i = c ? oi : i;                                                                                    \
-    }
-    VT_BEST_DPP(0xB1)
-    VT_BEST_DPP(0x4E)
-    VT_BEST_DPP(0x141)
-    VT_BEST_DPP(0x140)
-#undef VT_BEST_DPP
-    {
-        const auto rv = __builtin_amdgcn_permlane16_swap(__float_as_int(v), __float_as_int(v), false, false);
-        const auto ri = __builtin_amdgcn_permlane16_swap(i, i, false, false);
-        const bool c = better(__int_as_float(rv[0]), (int)ri[0], __int_as_float(rv[1]), (int)ri[1]);
-        v = __int_as_float(c ? rv[0] : rv[1]);
-        i = (int)(c ? ri[0] : ri[1]);
-    }
-    {
-        const auto rv = __builtin_amdgcn_permlane32_swap(__float_as_int(v), __float_as_int(v), false, false);
-        const auto ri = __builtin_amdgcn_permlane32_swap(i, i, false, false);
-        const bool c = better(__int_as_float(rv[0]), (int)ri[0], __int_as_float(rv[1]), (int)ri[1]);
-        v = __int_as_float(c ? rv[0] : rv[1]);
-        i = (int)(c ? ri[0] : ri[1]);
-    }
+    const float bv = wave_max(v);
+    const int cand = (v == bv) ? i : kIdxNone;
+    i = wave_min_i(cand);
+    v = bv;
 }
 
 // Softmax partial (m, s) with s = sum exp(z - m) over some set; the empty set is (-inf, 0).
@@ -291,21 +287,21 @@ __device__ __forceinline__ float row16_sum(float x, int lane)
     return x;
 }
 
+__device__ __forceinline__ int row16_min_i(int x)
+{
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false));
+    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xf, 0xf, false));
+    return x;
+}
+
 __device__ __forceinline__ void row16_best(float& v, int& i)
 {
-#define VT_BEST_DPP(CTRL)                                                                                  \
-    {                                                                                                      \
-        const float ov = __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xf, 0xf, false)); \
-        const int oi = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);                           \
-        const bool c = better(ov, oi, v, i);                                                               \
-        v = c ? ov : v;                                                                                    \
-        i = c ? oi : i;                                                                                    \
-    }
-    VT_BEST_DPP(0xB1)
-    VT_BEST_DPP(0x4E)
-    VT_BEST_DPP(0x141)
-    VT_BEST_DPP(0x140)
-#undef VT_BEST_DPP
+    const float bv = row16_max(v);
+    const int cand = (v == bv) ? i : kIdxNone;
+    i = row16_min_i(cand);
+    v = bv;
 }
 
 // Combine the softmax partials of the 16 lanes of a row (inactive lanes pass (-inf, 0)).
