@@ -268,6 +268,69 @@ __device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane
     }
 }
 
+// k-way merge by one wave of up to 4*64 sorted candidate lists parked in LDS: list t occupies
+// lv/li[t * (KP + 1) .. + KP) (odd stride: conflict-free column access), an empty list has the
+// empty marker at its head.  Lane l looks after lists l, l+64, l+128, l+192 (NSLOT of them) and
+// keeps only their current heads in registers; a round takes the wave-wide best head and the
+// owning lane advances that list's read position.  Candidate indices are distinct across
+// lists, so exactly one lane owns the winner.  Lane q returns the q-th best (q < rounds).
+template <int KP, int NSLOT>
+__device__ __forceinline__ void wave_walk_merge(const float* lv, const int* li, int nlists, int rounds, int lane,
+                                                float& outv, int& outi)
+{
+    constexpr int S = KP + 1;
+    float hv[NSLOT];
+    int hi[NSLOT];
+#pragma unroll
+    for (int sl = 0; sl < NSLOT; ++sl) {
+        const int t = sl * kWave + lane;
+        const bool ok = t < nlists;
+        hv[sl] = ok ? lv[t * S] : neg_inf();
+        hi[sl] = ok ? li[t * S] : kIdxNone;
+    }
+    int pos = 0;  // read positions of the NSLOT lists, 8 bits each
+    outv = neg_inf();
+    outi = kIdxNone;
+#pragma unroll 1
+    for (int q = 0; q < rounds; ++q) {
+        float bv = hv[0];
+        int bi = hi[0];
+        int bs = 0;
+#pragma unroll
+        for (int sl = 1; sl < NSLOT; ++sl) {
+            const bool c = better(hv[sl], hi[sl], bv, bi);
+            bv = c ? hv[sl] : bv;
+            bi = c ? hi[sl] : bi;
+            bs = c ? sl : bs;
+        }
+        float wv = bv;
+        int wi = bi;
+        wave_best(wv, wi);
+        if (lane == q) {
+            outv = wv;
+            outi = wi;
+        }
+        if (wi == kIdxNone)  // wave-uniform: nothing left anywhere
+            break;
+        if (bi == wi) {
+            pos += 1 << (8 * bs);
+            const int np = (pos >> (8 * bs)) & 0xff;
+            const int t = bs * kWave + lane;
+            float nv = neg_inf();
+            int ni = kIdxNone;
+            if (np < KP) {
+                nv = lv[t * S + np];
+                ni = li[t * S + np];
+            }
+#pragma unroll
+            for (int sl = 0; sl < NSLOT; ++sl) {
+                hv[sl] = (sl == bs) ? nv : hv[sl];
+                hi[sl] = (sl == bs) ? ni : hi[sl];
+            }
+        }
+    }
+}
+
 // ---- the same reductions inside one DPP row (16 consecutive lanes), DPP only ----
 __device__ __forceinline__ float row16_max(float x)
 {

@@ -23,8 +23,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                                                               float* __restrict__ lse_out)
 {
     constexpr int NW = kMergeThreads / kWave;
-    __shared__ float sm_val[NW][KP];
-    __shared__ int sm_idx[NW][KP];
+    __shared__ float sm_val[KP > 16 ? NW : 1][KP];  // per-wave results (long lists only)
+    __shared__ int sm_idx[KP > 16 ? NW : 1][KP];
     __shared__ float2 sm_stat[NW];
 
     const int r = blockIdx.x;
@@ -87,10 +87,20 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         const float* pv = part_val + slot * KP;
         const int32_t* pi = part_idx + slot * KP;
         if (first) {  // the first list a thread keeps is taken as it is (partial lists are sorted)
+            if constexpr (KP % 4 == 0) {  // workspace and its sections are 16-byte aligned: 128-bit loads
 #pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                L.v[q] = pv[q];
-                L.i[q] = pi[q];
+                for (int q = 0; q < KP; q += 4) {
+                    const float4 xv = *reinterpret_cast<const float4*>(pv + q);
+                    const int4 xi = *reinterpret_cast<const int4*>(pi + q);
+                    L.v[q] = xv.x, L.v[q + 1] = xv.y, L.v[q + 2] = xv.z, L.v[q + 3] = xv.w;
+                    L.i[q] = xi.x, L.i[q + 1] = xi.y, L.i[q + 2] = xi.z, L.i[q + 3] = xi.w;
+                }
+            } else {
+#pragma unroll
+                for (int q = 0; q < KP; ++q) {
+                    L.v[q] = pv[q];
+                    L.i[q] = pi[q];
+                }
             }
             first = false;
         } else {  // later lists: sorted, so stop at the first entry that cannot enter
@@ -104,35 +114,88 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
             }
         }
     };
+    if constexpr (KP <= 16) {
+        // The lists that pass the bound (a few dozen as a rule) are queued in LDS and dealt out
+        // again one per thread, so their loads are all in flight together instead of one list
+        // after the other in the threads that happened to own several.  A list that does not fit
+        // the queue is merged on the spot by its owner.
+        constexpr int QCAP = 2048;
+        __shared__ int sm_queue[QCAP];
+        __shared__ int sm_qn;
+        if (tid == 0)
+            sm_qn = 0;
+        __syncthreads();
+        auto offer = [&](int p, float best) {
+            if (best < bound)
+                return;
+            const int slot = atomicAdd(&sm_qn, 1);
+            if (slot < QCAP)
+                sm_queue[slot] = p;
+            else
+                take_list(p);
+        };
 #pragma unroll
-    for (int c = 0; c < CH; ++c) {
-        const int p = c * kMergeThreads + tid;
-        if (p < P && !(best0[c] < bound) && !(best0[c] < L.v[KP - 1]))
-            take_list(p);
-    }
-    for (int p = CH * kMergeThreads + tid; p < P; p += kMergeThreads) {  // beyond the first batch (very large P)
-        const float best = part_stat[(size_t)r * P + p].x;
-        if (!(best < bound) && !(best < L.v[KP - 1]))
-            take_list(p);
+        for (int c = 0; c < CH; ++c) {
+            const int p = c * kMergeThreads + tid;
+            if (p < P)
+                offer(p, best0[c]);
+        }
+        for (int p = CH * kMergeThreads + tid; p < P; p += kMergeThreads)  // beyond the first batch (very large P)
+            offer(p, part_stat[(size_t)r * P + p].x);
+        __syncthreads();
+        const int qn = sm_qn < QCAP ? sm_qn : QCAP;
+        for (int q = tid; q < qn; q += kMergeThreads)
+            take_list(sm_queue[q]);
+    } else {
+#pragma unroll
+        for (int c = 0; c < CH; ++c) {
+            const int p = c * kMergeThreads + tid;
+            if (p < P && !(best0[c] < L.v[KP - 1]))
+                take_list(p);
+        }
+        for (int p = CH * kMergeThreads + tid; p < P; p += kMergeThreads) {  // beyond the first batch (very large P)
+            const float best = part_stat[(size_t)r * P + p].x;
+            if (!(best < L.v[KP - 1]))
+                take_list(p);
+        }
     }
 
     wave_stat_merge(m, s, true);
-    float ov;
-    int oi;
-    wave_merge<KP>(L, true, lane, ov, oi, k);
-    if (lane < KP) {
-        sm_val[wave][lane] = ov;
-        sm_idx[wave][lane] = oi;
-    }
     if (lane == 0)
         sm_stat[wave] = make_float2(m, s);
-    __syncthreads();
-
-    if (wave == 0) {
+    float ov;
+    int oi;
+    if constexpr (KP <= 16) {
+        // Every thread parks its (sorted) list in LDS; wave 0 merges all of them in k rounds,
+        // touching only list heads.
+        constexpr int S = KP + 1;
+        __shared__ float sl_val[kMergeThreads * S];
+        __shared__ int sl_idx[kMergeThreads * S];
+        sl_val[tid * S] = L.v[0];
+        sl_idx[tid * S] = L.i[0];
+        if (L.i[0] != kIdxNone) {
+#pragma unroll
+            for (int q = 1; q < KP; ++q) {
+                sl_val[tid * S + q] = L.v[q];
+                sl_idx[tid * S + q] = L.i[q];
+            }
+        }
+        __syncthreads();
+        if (wave != 0)
+            return;
+        wave_walk_merge<KP, NW>(sl_val, sl_idx, kMergeThreads, k, lane, ov, oi);
+    } else {
+        wave_merge<KP>(L, true, lane, ov, oi, k);
+        if (lane < KP) {
+            sm_val[wave][lane] = ov;
+            sm_idx[wave][lane] = oi;
+        }
+        __syncthreads();
+        if (wave != 0)
+            return;
         const bool act = lane < NW;
         TopList<KP> T;
         T.clear();
-        float mv = neg_inf(), sv = 0.0f;
         if (act) {
 #pragma unroll
             for (int q = 0; q < KP; ++q) {  // slots k..KP-1 were not produced: leave them empty
@@ -141,11 +204,15 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                     T.i[q] = sm_idx[lane][q];
                 }
             }
-            mv = sm_stat[lane].x;
-            sv = sm_stat[lane].y;
         }
-        wave_stat_merge(mv, sv, act);
         wave_merge<KP>(T, act, lane, ov, oi, k);
+    }
+
+    {
+        const bool act = lane < NW;
+        float mv = act ? sm_stat[act ? lane : 0].x : neg_inf();
+        float sv = act ? sm_stat[act ? lane : 0].y : 0.0f;
+        wave_stat_merge(mv, sv, act);
         const float lse = mv + __logf(sv);
         if (lane < k) {
             out_ids[(size_t)r * k + lane] = (oi != kIdxNone) ? d2t[oi] : -1;
