@@ -150,22 +150,63 @@ __device__ __forceinline__ float xchg_f(float x, int lane)
     return __int_as_float(xchg_i<OFF>(__float_as_int(x), lane));
 }
 
-__device__ __forceinline__ float wave_max(float x)
+// Order-preserving map of a (non-NaN) float onto int32: a > b <=> key(a) > key(b); -0 and +0
+// share a key.  Integer max/min fold their DPP operand into one instruction and need no NaN
+// quieting, so the arg-max rounds below run on keys.
+__device__ __forceinline__ int f2key(float x)
 {
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0xB1, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x4E, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x141, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x140, 0xf, 0xf, false)));
+    const int b = __float_as_int(x + 0.0f);
+    return b ^ ((b >> 31) & 0x7fffffff);
+}
+__device__ __forceinline__ float key2f(int k) { return __int_as_float(k ^ ((k >> 31) & 0x7fffffff)); }
+constexpr int kKeyNone = (int)0x807fffff;  // key of -inf
+
+// Reductions over the 16 lanes of a DPP row: pairs (quad_perm), quads, mirrored halves of 8,
+// mirrored row.  Every lane returns the result.
+__device__ __forceinline__ int row16_max_i(int x)
+{
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true));
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true));
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true));
+    x = max(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true));
+    return x;
+}
+__device__ __forceinline__ int row16_min_i(int x)
+{
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x141, 0xf, 0xf, true));
+    x = min(x, __builtin_amdgcn_mov_dpp(x, 0x140, 0xf, 0xf, true));
+    return x;
+}
+__device__ __forceinline__ int wave_max_i(int x)
+{
+    x = row16_max_i(x);
     {
-        const auto r = __builtin_amdgcn_permlane16_swap(__float_as_int(x), __float_as_int(x), false, false);
-        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        x = max((int)r[0], (int)r[1]);
     }
     {
-        const auto r = __builtin_amdgcn_permlane32_swap(__float_as_int(x), __float_as_int(x), false, false);
-        x = fmaxf(__int_as_float(r[0]), __int_as_float(r[1]));
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        x = max((int)r[0], (int)r[1]);
     }
     return x;
 }
+__device__ __forceinline__ int wave_min_i(int x)
+{
+    x = row16_min_i(x);
+    {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        x = min((int)r[0], (int)r[1]);
+    }
+    {
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        x = min((int)r[0], (int)r[1]);
+    }
+    return x;
+}
+
+__device__ __forceinline__ float wave_max(float x) { return key2f(wave_max_i(f2key(x))); }
 
 // Sum over the wave; every lane returns the same bits (a fixed tree: xor 1, 2, 4, 8, 16, 32).
 __device__ __forceinline__ float wave_sum(float x)
@@ -186,32 +227,41 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-__device__ __forceinline__ int wave_min_i(int x)
-{
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xf, 0xf, false));
-    {
-        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-        x = min((int)r[0], (int)r[1]);
-    }
-    {
-        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-        x = min((int)r[0], (int)r[1]);
-    }
-    return x;
-}
-
 // Best (logit, index) pair over the wave under the strict order; every lane returns it.
 // Two cheap reductions instead of one over pairs: the largest logit, then the smallest index
 // among the lanes that hold it.
+__device__ __forceinline__ void wave_best_key(int& kv, int& i)
+{
+    const int bk = wave_max_i(kv);
+    const int cand = (kv == bk) ? i : kIdxNone;
+    i = wave_min_i(cand);
+    kv = bk;
+}
 __device__ __forceinline__ void wave_best(float& v, int& i)
 {
-    const float bv = wave_max(v);
-    const int cand = (v == bv) ? i : kIdxNone;
-    i = wave_min_i(cand);
-    v = bv;
+    int kv = f2key(v);
+    wave_best_key(kv, i);
+    v = key2f(kv);
+}
+
+// The same when lane order is index order (a lower lane never holds a higher index among
+// equal keys): the best key comes back wave-uniform through four lane reads of the row maxima,
+// and the winner is the lowest lane that holds it.  Needs all 64 lanes active.
+__device__ __forceinline__ int wave_max_i_uniform(int x)
+{
+    x = row16_max_i(x);
+    const int a = __builtin_amdgcn_readlane(x, 0);
+    const int b = __builtin_amdgcn_readlane(x, 16);
+    const int c = __builtin_amdgcn_readlane(x, 32);
+    const int d = __builtin_amdgcn_readlane(x, 48);
+    return max(max(a, b), max(c, d));
+}
+__device__ __forceinline__ void wave_best_ordered(int kv, int i, int& best_key, int& best_idx, int& winner)
+{
+    best_key = wave_max_i_uniform(kv);
+    const unsigned long long tie = __ballot(kv == best_key);
+    winner = (int)__builtin_ctzll(tie);
+    best_idx = __builtin_amdgcn_readlane(i, winner);
 }
 
 // Softmax partial (m, s) with s = sum exp(z - m) over some set; the empty set is (-inf, 0).
@@ -268,78 +318,85 @@ __device__ __forceinline__ void wave_merge(TopList<KP>& L, bool active, int lane
     }
 }
 
-// k-way merge by one wave of up to 4*64 sorted candidate lists parked in LDS: list t occupies
-// lv/li[t * (KP + 1) .. + KP) (odd stride: conflict-free column access), an empty list has the
-// empty marker at its head.  Lane l looks after lists l, l+64, l+128, l+192 (NSLOT of them) and
-// keeps only their current heads in registers; a round takes the wave-wide best head and the
-// owning lane advances that list's read position.  Candidate indices are distinct across
-// lists, so exactly one lane owns the winner.  Lane q returns the q-th best (q < rounds).
-template <int KP, int NSLOT>
+// k-way merge by one wave of up to NSLOT*64 sorted candidate lists parked in LDS: list t
+// occupies lv/li[t * (KP + 1) .. + KP) (odd stride: conflict-free column access), an empty list
+// has the empty marker at its head.  A lane keeps only the current heads of its NSLOT lists in
+// registers; a round takes the wave-wide best head and the owning lane advances that list's
+// read position.  Candidate indices are distinct across lists, so exactly one lane owns the
+// winner.  Lane q returns the q-th best (q < rounds).
+//
+// ORDERED: every index in list t is below every index in list t+1.  Lane l then looks after
+// lists NSLOT*l .. NSLOT*l+NSLOT-1, ties resolve by position alone and the cheaper
+// wave_best_ordered applies.  Otherwise lane l has lists l, l+64, ... and ties compare indices.
+template <int KP, int NSLOT, bool ORDERED>
 __device__ __forceinline__ void wave_walk_merge(const float* lv, const int* li, int nlists, int rounds, int lane,
                                                 float& outv, int& outi)
 {
     constexpr int S = KP + 1;
-    float hv[NSLOT];
+    int hk[NSLOT];  // heads as order-preserving keys
     int hi[NSLOT];
 #pragma unroll
     for (int sl = 0; sl < NSLOT; ++sl) {
-        const int t = sl * kWave + lane;
+        const int t = ORDERED ? lane * NSLOT + sl : sl * kWave + lane;
         const bool ok = t < nlists;
-        hv[sl] = ok ? lv[t * S] : neg_inf();
+        hk[sl] = ok ? f2key(lv[t * S]) : kKeyNone;
         hi[sl] = ok ? li[t * S] : kIdxNone;
     }
     int pos = 0;  // read positions of the NSLOT lists, 8 bits each
-    outv = neg_inf();
+    int outk = kKeyNone;
     outi = kIdxNone;
 #pragma unroll 1
     for (int q = 0; q < rounds; ++q) {
-        float bv = hv[0];
+        int bk = hk[0];
         int bi = hi[0];
         int bs = 0;
 #pragma unroll
         for (int sl = 1; sl < NSLOT; ++sl) {
-            const bool c = better(hv[sl], hi[sl], bv, bi);
-            bv = c ? hv[sl] : bv;
+            const bool c = ORDERED ? (hk[sl] > bk) : ((hk[sl] > bk) || (hk[sl] == bk && hi[sl] < bi));
+            bk = c ? hk[sl] : bk;
             bi = c ? hi[sl] : bi;
             bs = c ? sl : bs;
         }
-        float wv = bv;
-        int wi = bi;
-        wave_best(wv, wi);
+        int wk, wi;
+        bool mine;
+        if constexpr (ORDERED) {
+            int winner;
+            wave_best_ordered(bk, bi, wk, wi, winner);
+            mine = lane == winner;
+        } else {
+            wk = bk;
+            wi = bi;
+            wave_best_key(wk, wi);
+            mine = bi == wi;
+        }
         if (lane == q) {
-            outv = wv;
+            outk = wk;
             outi = wi;
         }
         if (wi == kIdxNone)  // wave-uniform: nothing left anywhere
             break;
-        if (bi == wi) {
+        if (mine) {
             pos += 1 << (8 * bs);
             const int np = (pos >> (8 * bs)) & 0xff;
-            const int t = bs * kWave + lane;
-            float nv = neg_inf();
+            const int t = ORDERED ? lane * NSLOT + bs : bs * kWave + lane;
+            int nk = kKeyNone;
             int ni = kIdxNone;
             if (np < KP) {
-                nv = lv[t * S + np];
+                nk = f2key(lv[t * S + np]);
                 ni = li[t * S + np];
             }
 #pragma unroll
             for (int sl = 0; sl < NSLOT; ++sl) {
-                hv[sl] = (sl == bs) ? nv : hv[sl];
+                hk[sl] = (sl == bs) ? nk : hk[sl];
                 hi[sl] = (sl == bs) ? ni : hi[sl];
             }
         }
     }
+    outv = key2f(outk);
 }
 
 // ---- the same reductions inside one DPP row (16 consecutive lanes), DPP only ----
-__device__ __forceinline__ float row16_max(float x)
-{
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0xB1, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x4E, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x141, 0xf, 0xf, false)));
-    x = fmaxf(x, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), 0x140, 0xf, 0xf, false)));
-    return x;
-}
+__device__ __forceinline__ float row16_max(float x) { return key2f(row16_max_i(f2key(x))); }
 
 __device__ __forceinline__ float row16_sum(float x, int lane)
 {
@@ -350,21 +407,13 @@ __device__ __forceinline__ float row16_sum(float x, int lane)
     return x;
 }
 
-__device__ __forceinline__ int row16_min_i(int x)
-{
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x141, 0xf, 0xf, false));
-    x = min(x, __builtin_amdgcn_update_dpp(x, x, 0x140, 0xf, 0xf, false));
-    return x;
-}
-
 __device__ __forceinline__ void row16_best(float& v, int& i)
 {
-    const float bv = row16_max(v);
-    const int cand = (v == bv) ? i : kIdxNone;
+    const int kv = f2key(v);
+    const int bk = row16_max_i(kv);
+    const int cand = (kv == bk) ? i : kIdxNone;
     i = row16_min_i(cand);
-    v = bv;
+    v = key2f(bk);
 }
 
 // Combine the softmax partials of the 16 lanes of a row (inactive lanes pass (-inf, 0)).

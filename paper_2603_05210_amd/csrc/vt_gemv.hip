@@ -12,6 +12,7 @@
 // of the range by k rounds of a wave-wide arg-max under the (logit, lower index) order.  One
 // partial per (row, workgroup) goes to the merge kernel.
 #include <atomic>
+#include <type_traits>
 
 #include "vt_device.h"
 #include "vt_internal.h"
@@ -50,80 +51,61 @@ __device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_lo
 __device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 static __device__ unsigned int g_ticket[kTicketSlots];
 
-// Final merge by the last workgroup: level 1 merges the P per-workgroup partials of a row in
-// groups of 16 lists (one 16-lane DPP row per group, 64 groups at a time over the 16 waves),
-// level 2 merges the <= 16 results per row and emits ids (through d2t) and log-probabilities.
+// Final merge by the last workgroup: the partial lists of every row are fetched into LDS (all
+// threads, coalesced), 256 threads per hidden-state row reduce the row's softmax partials, then
+// one wave per row merges the row's lists by walking their heads (k rounds) and emits ids
+// (through d2t) and log-probabilities.
+constexpr int kFusedMaxRows = kGemvThreads / 256;
 template <int KP>
 __device__ __forceinline__ void fused_final_merge(const GemvArgs& a, char* lds, int tid)
 {
+    constexpr int S = KP + 1;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int sub = lane & 15;
-    const int nchunks = (a.P + 15) >> 4;  // <= 16
-    const int ngroups = a.rows * nchunks;
-    float* l1_val = reinterpret_cast<float*>(lds);                 // [ngroups][KP]
-    int* l1_idx = reinterpret_cast<int*>(l1_val + ngroups * KP);   // [ngroups][KP]
-    float2* l1_stat = reinterpret_cast<float2*>(l1_idx + ngroups * KP);
+    const int row = tid >> 8;
+    const int p = tid & 255;
+    float* lv = reinterpret_cast<float*>(lds);                 // [rows][256][S]
+    int* li = reinterpret_cast<int*>(lv + a.rows * 256 * S);   // [rows][256][S]
+    float2* wstat = reinterpret_cast<float2*>(li + a.rows * 256 * S);  // [waves]
 
-    for (int base = 0; base < ngroups; base += kGemvWaves * 4) {
-        const int gidx = base + wave * 4 + (lane >> 4);
-        const bool gok = gidx < ngroups;
-        const int row = gok ? gidx / nchunks : 0;
-        const int chunk = gidx - row * nchunks;
-        const int p = chunk * 16 + sub;
-        TopList<KP> L;
-        L.clear();
-        float m = neg_inf(), s = 0.0f;
-        if (gok && p < a.P) {
-            const size_t slot = (size_t)row * a.P + p;
-#pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                L.v[q] = ld_dev(a.part_val + slot * KP + q);
-                L.i[q] = ld_dev(a.part_idx + slot * KP + q);
-            }
-            m = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot));
-            s = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot) + 1);
-        }
-        row16_stat_merge(m, s, lane);
-        float ov;
-        int oi;
-        row16_merge<KP>(L, a.k, lane, ov, oi);
-        if (gok) {
-            if (sub < KP) {
-                l1_val[gidx * KP + sub] = ov;
-                l1_idx[gidx * KP + sub] = oi;
-            }
-            if (sub == 0)
-                l1_stat[gidx] = make_float2(m, s);
+    // lists: consecutive threads fetch consecutive words of the row's [P][KP] arrays
+    const int kp_shift = ilog2(KP);
+    for (int r = 0; r < a.rows; ++r) {
+        const size_t off = (size_t)r * a.P * KP;
+        for (int e = tid; e < a.P * KP; e += kGemvThreads) {
+            const float v = ld_dev(a.part_val + off + e);
+            const int ix = ld_dev(a.part_idx + off + e);
+            const int at = (r * 256 + (e >> kp_shift)) * S + (e & (KP - 1));
+            lv[at] = v;
+            li[at] = ix;
         }
     }
+    const bool ok = row < a.rows && p < a.P;
+    float m = neg_inf(), s = 0.0f;
+    if (ok) {
+        const size_t slot = (size_t)row * a.P + p;
+        m = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot));
+        s = ld_dev(reinterpret_cast<const float*>(a.part_stat + slot) + 1);
+    }
+    wave_stat_merge(m, s, ok);  // the four waves of a row each reduce their share
+    if (lane == 0)
+        wstat[wave] = make_float2(m, s);
     __syncthreads();
 
-    const int row = wave * 4 + (lane >> 4);
-    if (row < a.rows) {  // whole 16-lane rows are in or out together
-        TopList<KP> L;
-        L.clear();
-        float m = neg_inf(), s = 0.0f;
-        if (sub < nchunks) {
-            const int gidx = row * nchunks + sub;
-#pragma unroll
-            for (int q = 0; q < KP; ++q) {
-                L.v[q] = l1_val[gidx * KP + q];
-                L.i[q] = l1_idx[gidx * KP + q];
-            }
-            m = l1_stat[gidx].x;
-            s = l1_stat[gidx].y;
-        }
-        row16_stat_merge(m, s, lane);
+    if ((wave & 3) == 0 && row < a.rows) {
         float ov;
         int oi;
-        row16_merge<KP>(L, a.k, lane, ov, oi);
-        const float lse = m + __logf(s);
-        if (sub < a.k) {
-            a.out_ids[(size_t)row * a.k + sub] = (oi != kIdxNone) ? a.d2t[oi] : -1;
-            a.out_logp[(size_t)row * a.k + sub] = ov - lse;
+        wave_walk_merge<KP, 4, true>(lv + row * 256 * S, li + row * 256 * S, a.P, a.k, lane, ov, oi);
+        const bool act = lane < 4;
+        float mv = act ? wstat[wave + (lane & 3)].x : neg_inf();
+        float sv = act ? wstat[wave + (lane & 3)].y : 0.0f;
+        wave_stat_merge(mv, sv, act);
+        const float lse = mv + __logf(sv);
+        if (lane < a.k) {
+            a.out_ids[(size_t)row * a.k + lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
+            a.out_logp[(size_t)row * a.k + lane] = ov - lse;
         }
-        if (sub == 0 && a.lse_out != nullptr)
+        if (lane == 0 && a.lse_out != nullptr)
             a.lse_out[row] = lse;
     }
 }
@@ -158,7 +140,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
 {
     constexpr int NP = NR * J;      // (hidden row, W_sub row) pairs reduced together
     constexpr int CL = kWave / NP;  // lanes that end up holding the same pair
-    constexpr int VPL = kGemvMaxRowsPerBlock / kWave;  // logits per lane in the selection
+    static_assert(kGemvMaxRowsPerBlock <= 8 * kWave, "at most 8 logits per lane in the selection");
     static_assert(NP <= kWave && (NP & (NP - 1)) == 0, "pairs per group must be a power of two <= 64");
     static_assert(NR <= kGemvWaves, "one wave per hidden-state row in the selection");
     extern __shared__ u32x4 smem[];
@@ -261,46 +243,69 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
     // ---- selection over this workgroup's range: wave r handles hidden-state row r ----
     if (wave < a.rows) {
         const int r = wave;
-        float v[VPL];
-        float mloc = neg_inf();
-#pragma unroll
-        for (int i = 0; i < VPL; ++i) {
-            const int e = lane + i * kWave;
-            v[i] = (e < n_local) ? zbuf[r * a.rpb + e] : neg_inf();
-            mloc = fmaxf(mloc, v[i]);
-        }
-        const float m = wave_max(mloc);
-        float sloc = 0.0f;
-#pragma unroll
-        for (int i = 0; i < VPL; ++i)
-            sloc += __expf(v[i] - m);  // n_local >= 1, so m is finite
-        const float s = wave_sum(sloc);
-
+        float m = 0.0f, s = 0.0f;
         float outv = neg_inf();
         int outi = kIdxNone;
-#pragma unroll 1
-        for (int q = 0; q < a.k; ++q) {
-            // best of this lane's logits: the first maximum has the lowest index
-            float bv = v[0];
-            int bi = 0;
+        // VPL = logits per lane: the smallest of 1, 2, 4, 8 that covers the workgroup's range
+        auto select = [&](auto vpl_c) {
+            constexpr int VPL = decltype(vpl_c)::value;
+            // lane l takes logits l*VPL .. l*VPL+VPL-1 of the range: lane order is index order
+            float v[VPL];
+            float mloc = neg_inf();
 #pragma unroll
-            for (int i = 1; i < VPL; ++i) {
-                const bool c = v[i] > bv;
-                bv = c ? v[i] : bv;
-                bi = c ? i : bi;
+            for (int i = 0; i < VPL; ++i) {
+                const int e = lane * VPL + i;
+                v[i] = (e < n_local) ? zbuf[r * a.rpb + e] : neg_inf();
+                mloc = fmaxf(mloc, v[i]);
             }
-            int gi = (bv > neg_inf()) ? (j_lo + lane + bi * kWave) : kIdxNone;
-            wave_best(bv, gi);
-            if (lane == q) {
-                outv = bv;
-                outi = gi;
-            }
-            // the owner retires the winner
-            const int mine = gi - j_lo - lane;  // = i * 64 for the owner's slot i
+            m = wave_max(mloc);
+            float sloc = 0.0f;
 #pragma unroll
             for (int i = 0; i < VPL; ++i)
-                v[i] = (mine == i * kWave) ? neg_inf() : v[i];
-        }
+                sloc += __expf(v[i] - m);  // n_local >= 1, so m is finite
+            s = wave_sum(sloc);
+
+            // k rounds of a wave-wide arg-max on order-preserving integer keys
+            int kv[VPL];
+#pragma unroll
+            for (int i = 0; i < VPL; ++i)
+                kv[i] = f2key(v[i]);
+            int outk = kKeyNone;
+#pragma unroll 1
+            for (int q = 0; q < a.k; ++q) {
+                // best of this lane's logits: the first maximum has the lowest index
+                int bk = kv[0];
+                int bi = 0;
+#pragma unroll
+                for (int i = 1; i < VPL; ++i) {
+                    const bool c = kv[i] > bk;
+                    bk = c ? kv[i] : bk;
+                    bi = c ? i : bi;
+                }
+                const int gi = (bk != kKeyNone) ? (j_lo + lane * VPL + bi) : kIdxNone;
+                int wk, wi, winner;
+                wave_best_ordered(bk, gi, wk, wi, winner);
+                if (lane == q) {
+                    outk = wk;
+                    outi = wi;
+                }
+                // the owner retires the winner
+                const int gone = (lane == winner) ? bi : -1;
+#pragma unroll
+                for (int i = 0; i < VPL; ++i)
+                    kv[i] = (gone == i) ? kKeyNone : kv[i];
+            }
+            outv = key2f(outk);
+        };
+        const int per_lane = (a.rpb + kWave - 1) / kWave;
+        if (per_lane <= 1)
+            select(std::integral_constant<int, 1>{});
+        else if (per_lane <= 2)
+            select(std::integral_constant<int, 2>{});
+        else if (per_lane <= 4)
+            select(std::integral_constant<int, 4>{});
+        else
+            select(std::integral_constant<int, 8>{});
         const size_t slot = (size_t)r * a.P + blockIdx.x;
         if (lane < a.KP) {  // slots k..KP-1 carry the empty marker
             st_dev(a.part_val + slot * a.KP + lane, outv);
@@ -344,8 +349,10 @@ template <int NR, int J, bool DOT2>
 static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
     size_t lds = (size_t)NR * ga.nchunk * sizeof(u32x4) + (size_t)NR * ga.rpb * sizeof(float);
-    if (ga.fused) {  // staging of the level-1 results of the fused merge
-        const size_t l1 = (size_t)ga.rows * ((ga.P + 15) / 16) * ((size_t)ga.KP * 8 + 8);
+    if (ga.fused) {  // the fused merge parks up to 256 lists per row in LDS, plus per-wave statistics
+        if (ga.rows > kFusedMaxRows || ga.P > 256 || ga.KP > 16)
+            return hipErrorInvalidValue;
+        const size_t l1 = (size_t)ga.rows * 256 * ((size_t)ga.KP + 1) * 8 + kGemvWaves * sizeof(float2);
         lds = lds > l1 ? lds : l1;
     }
     auto kern = gemv_head_kernel<NR, J, DOT2>;

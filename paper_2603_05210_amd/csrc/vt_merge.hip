@@ -183,7 +183,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         __syncthreads();
         if (wave != 0)
             return;
-        wave_walk_merge<KP, NW>(sl_val, sl_idx, kMergeThreads, k, lane, ov, oi);
+        wave_walk_merge<KP, NW, false>(sl_val, sl_idx, kMergeThreads, k, lane, ov, oi);
     } else {
         wave_merge<KP>(L, true, lane, ov, oi, k);
         if (lane < KP) {
