@@ -92,13 +92,13 @@ __device__ __forceinline__ void fused_final_merge(const GemvArgs& a, char* lds, 
         wstat[wave] = make_float2(m, s);
     __syncthreads();
 
-    if ((wave & 3) == 0 && row < a.rows) {
+    if ((wave & 3) == (row & 3) && row < a.rows) {  // one wave per row, each on a SIMD of its own
         float ov;
         int oi;
         wave_walk_merge<KP, 4, true>(lv + row * 256 * S, li + row * 256 * S, a.P, a.k, lane, ov, oi);
         const bool act = lane < 4;
-        float mv = act ? wstat[wave + (lane & 3)].x : neg_inf();
-        float sv = act ? wstat[wave + (lane & 3)].y : 0.0f;
+        float mv = act ? wstat[(wave & ~3) + (lane & 3)].x : neg_inf();
+        float sv = act ? wstat[(wave & ~3) + (lane & 3)].y : 0.0f;
         wave_stat_merge(mv, sv, act);
         const float lse = mv + __logf(sv);
         if (lane < a.k) {
