@@ -50,6 +50,9 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         p.P = p.blocks;
         // fusing pays while one workgroup can finish all rows in one pass
         p.fused = (rows <= 2 && p.P <= 256 && p.KP <= 16) ? 1 : 0;
+        // five rows or more: matrix-core variant (measured: 93.6 vs 104 us at 8 rows, 96 vs 165 us at
+        // 16; the dot-product form wins up to 4 rows), while every wave gets a 16-row group
+        p.mfma = (rows >= 5 && H % 256 == 0 && p.rpb >= 16 * kGemvWaves) ? 1 : 0;
     } else {
         p.regime = 1;
         p.tile = gemm_pick_tile((int)rows, (int)H, (int)Vd, p.KP);

@@ -135,111 +135,15 @@ __device__ __forceinline__ float dot8(const u32x4& w, const u32x4& x, float acc)
     return acc;
 }
 
-template <int NR, int J, bool DOT2>
-__global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
+// What every workgroup of the streaming kernels does once the logits of its range
+// [j_lo, j_lo + n_local) are in LDS (zbuf[row][rpb]): per hidden-state row the softmax
+// partial and the k best of the range, written as one partial result; then, when the call is
+// fused, the last workgroup to arrive merges all partial results and emits the outputs.
+__device__ __forceinline__ void block_tail(const GemvArgs& a, u32x4* smem, const float* zbuf, int tid, int j_lo,
+                                           int n_local)
 {
-    constexpr int NP = NR * J;      // (hidden row, W_sub row) pairs reduced together
-    constexpr int CL = kWave / NP;  // lanes that end up holding the same pair
-    static_assert(kGemvMaxRowsPerBlock <= 8 * kWave, "at most 8 logits per lane in the selection");
-    static_assert(NP <= kWave && (NP & (NP - 1)) == 0, "pairs per group must be a power of two <= 64");
-    static_assert(NR <= kGemvWaves, "one wave per hidden-state row in the selection");
-    extern __shared__ u32x4 smem[];
-
-    const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
-    const int nchunk = a.nchunk;
-    float* zbuf = reinterpret_cast<float*>(smem + NR * nchunk);  // [NR][rpb]
-
-    const int p_l = (NP > 1) ? (lane >> (6 - ilog2(NP))) : 0;  // pair this lane ends up with
-    const int r_l = p_l / J;
-    const int jj_l = p_l - r_l * J;
-    const bool owner = (lane & (CL - 1)) == 0;
-
-    const int j_lo = blockIdx.x * a.rpb;
-    const int j_hi = (j_lo + a.rpb < a.Vd) ? j_lo + a.rpb : a.Vd;
-    const int n_local = j_hi - j_lo;
-    const int ngroups = (n_local + J - 1) / J;
-
-    // The wave walks positions (group g of J rows, 1 KiB column step t) in order and keeps the
-    // loads of the next position in flight while it multiplies the current one, also across
-    // the boundary between two groups.
-    const int T = (nchunk + kWave - 1) / kWave;
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    auto load_pos = [&](int gg, int tt, u32x4(&buf)[J]) {
-        const int c = lane + tt * kWave;
-        const int j0 = j_lo + gg * J;
-#pragma unroll
-        for (int jj = 0; jj < J; ++jj) {
-            const int j = (j0 + jj < a.Vd) ? j0 + jj : a.Vd - 1;
-            buf[jj] = (c < nchunk) ? __builtin_nontemporal_load(a.W + (size_t)j * nchunk + c) : zero4;
-        }
-    };
-    float acc[NR][J];
-#pragma unroll
-    for (int r = 0; r < NR; ++r)
-#pragma unroll
-        for (int jj = 0; jj < J; ++jj)
-            acc[r][jj] = 0.0f;
-
-    int g = wave, t = 0;
-    auto step = [&](u32x4(&cur)[J], u32x4(&nxt)[J]) {
-        int tn = t + 1, gn = g;
-        if (tn == T) {
-            tn = 0;
-            gn = g + kGemvWaves;
-        }
-        if (gn < ngroups)
-            load_pos(gn, tn, nxt);
-        int c = lane + t * kWave;
-        c = c < nchunk ? c : nchunk - 1;  // lanes past the row end hold zeros in cur
-#pragma unroll
-        for (int r = 0; r < NR; ++r) {
-            const u32x4 x = smem[r * nchunk + c];
-#pragma unroll
-            for (int jj = 0; jj < J; ++jj)
-                acc[r][jj] = dot8<DOT2>(cur[jj], x, acc[r][jj]);
-        }
-        if (t == T - 1) {
-            float pv[NP];
-#pragma unroll
-            for (int r = 0; r < NR; ++r)
-#pragma unroll
-                for (int jj = 0; jj < J; ++jj) {
-                    pv[r * J + jj] = acc[r][jj];
-                    acc[r][jj] = 0.0f;
-                }
-            const float z = reduce_pairs<NP>(pv, lane);
-            const int j = j_lo + g * J + jj_l;
-            if (owner && j < j_hi && r_l < a.rows) {
-                zbuf[r_l * a.rpb + (j - j_lo)] = z;
-                if (a.logits_out != nullptr)
-                    a.logits_out[(size_t)r_l * a.Vd + j] = z;
-            }
-        }
-        t = tn;
-        g = gn;
-    };
-    u32x4 bufA[J], bufB[J];
-    if (g < ngroups)
-        load_pos(g, 0, bufA);  // the first W_sub loads are in flight while the hidden states are staged
-
-    // hidden states -> LDS (rows beyond `rows` repeat the last one; their results are dropped)
-    for (int x = tid; x < NR * nchunk; x += kGemvThreads) {
-        const int r = x / nchunk;
-        const int c = x - r * nchunk;
-        const int rr = r < a.rows ? r : a.rows - 1;
-        smem[x] = a.h[(size_t)rr * nchunk + c];
-    }
-    __syncthreads();
-    while (g < ngroups) {
-        step(bufA, bufB);
-        if (g >= ngroups)
-            break;
-        step(bufB, bufA);
-    }
-    __syncthreads();
-
     // ---- selection over this workgroup's range: wave r handles hidden-state row r ----
     if (wave < a.rows) {
         const int r = wave;
@@ -346,6 +250,293 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
 }
 
 template <int NR, int J, bool DOT2>
+__global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
+{
+    constexpr int NP = NR * J;      // (hidden row, W_sub row) pairs reduced together
+    constexpr int CL = kWave / NP;  // lanes that end up holding the same pair
+    static_assert(kGemvMaxRowsPerBlock <= 8 * kWave, "at most 8 logits per lane in the selection");
+    static_assert(NP <= kWave && (NP & (NP - 1)) == 0, "pairs per group must be a power of two <= 64");
+    static_assert(NR <= kGemvWaves, "one wave per hidden-state row in the selection");
+    extern __shared__ u32x4 smem[];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nchunk = a.nchunk;
+    float* zbuf = reinterpret_cast<float*>(smem + NR * nchunk);  // [NR][rpb]
+
+    const int p_l = (NP > 1) ? (lane >> (6 - ilog2(NP))) : 0;  // pair this lane ends up with
+    const int r_l = p_l / J;
+    const int jj_l = p_l - r_l * J;
+    const bool owner = (lane & (CL - 1)) == 0;
+
+    const int j_lo = blockIdx.x * a.rpb;
+    const int j_hi = (j_lo + a.rpb < a.Vd) ? j_lo + a.rpb : a.Vd;
+    const int n_local = j_hi - j_lo;
+    const int ngroups = (n_local + J - 1) / J;
+
+    // The wave walks positions (group g of J rows, 1 KiB column step t) in order and keeps the
+    // loads of the next position in flight while it multiplies the current one, also across
+    // the boundary between two groups.
+    const int T = (nchunk + kWave - 1) / kWave;
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    auto load_pos = [&](int gg, int tt, u32x4(&buf)[J]) {
+        const int c = lane + tt * kWave;
+        const int j0 = j_lo + gg * J;
+#pragma unroll
+        for (int jj = 0; jj < J; ++jj) {
+            const int j = (j0 + jj < a.Vd) ? j0 + jj : a.Vd - 1;
+            buf[jj] = (c < nchunk) ? __builtin_nontemporal_load(a.W + (size_t)j * nchunk + c) : zero4;
+        }
+    };
+    float acc[NR][J];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int jj = 0; jj < J; ++jj)
+            acc[r][jj] = 0.0f;
+
+    int g = wave, t = 0;
+    auto step = [&](u32x4(&cur)[J], u32x4(&nxt)[J]) {
+        int tn = t + 1, gn = g;
+        if (tn == T) {
+            tn = 0;
+            gn = g + kGemvWaves;
+        }
+        if (gn < ngroups)
+            load_pos(gn, tn, nxt);
+        int c = lane + t * kWave;
+        c = c < nchunk ? c : nchunk - 1;  // lanes past the row end hold zeros in cur
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const u32x4 x = smem[r * nchunk + c];
+#pragma unroll
+            for (int jj = 0; jj < J; ++jj)
+                acc[r][jj] = dot8<DOT2>(cur[jj], x, acc[r][jj]);
+        }
+        if (t == T - 1) {
+            float pv[NP];
+#pragma unroll
+            for (int r = 0; r < NR; ++r)
+#pragma unroll
+                for (int jj = 0; jj < J; ++jj) {
+                    pv[r * J + jj] = acc[r][jj];
+                    acc[r][jj] = 0.0f;
+                }
+            const float z = reduce_pairs<NP>(pv, lane);
+            const int j = j_lo + g * J + jj_l;
+            if (owner && j < j_hi && r_l < a.rows) {
+                zbuf[r_l * a.rpb + (j - j_lo)] = z;
+                if (a.logits_out != nullptr)
+                    a.logits_out[(size_t)r_l * a.Vd + j] = z;
+            }
+        }
+        t = tn;
+        g = gn;
+    };
+    u32x4 bufA[J], bufB[J];
+    if (g < ngroups)
+        load_pos(g, 0, bufA);  // the first W_sub loads are in flight while the hidden states are staged
+
+    // hidden states -> LDS (rows beyond `rows` repeat the last one; their results are dropped)
+    for (int x = tid; x < NR * nchunk; x += kGemvThreads) {
+        const int r = x / nchunk;
+        const int c = x - r * nchunk;
+        const int rr = r < a.rows ? r : a.rows - 1;
+        smem[x] = a.h[(size_t)rr * nchunk + c];
+    }
+    __syncthreads();
+    while (g < ngroups) {
+        step(bufA, bufB);
+        if (g >= ngroups)
+            break;
+        step(bufB, bufA);
+    }
+    __syncthreads();
+
+    block_tail(a, smem, zbuf, tid, j_lo, n_local);
+}
+
+// Matrix-core variant for several hidden-state rows (2..16): the same row-split stream of
+// W_sub, but a wave takes 16 consecutive W_sub rows at a time and feeds them to
+// v_mfma_f32_16x16x32_bf16 as the A operand (lane l: row l%16, k-offset 8*(l/16) of the 32-wide
+// step), the hidden states (LDS, 16-byte pieces XOR-swizzled by row so that the 16 rows of a
+// step fall into distinct bank groups) as the B operand.  One MFMA, one 16-byte global load and
+// a few LDS accesses per lane per KiB of W_sub whatever the row count, and no cross-lane
+// reduction: lane l ends with the logits of hidden row l%16 for W_sub rows 4*(l/16)..+3 of
+// the group.  Needs H % 256 == 0 (8 KiB per wave and loop iteration).
+//
+// STAGED: global loads stay line-sized (a load instruction takes 128 contiguous bytes of each
+// of 8 rows; loading straight into the A layout touches 64 different lines per instruction and
+// is bound by the L1 tag rate), and a 2 KiB wave-private LDS buffer turns 16 rows x 128 bytes
+// into A fragments.  The direct form remains for shapes whose hidden states leave no LDS for
+// the staging buffers.
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+constexpr int kMfmaGroup = 16;   // W_sub rows per wave and pass
+constexpr int kMfmaUnroll = 8;   // KiB (load instructions) per wave and loop iteration
+constexpr int kMfmaStage = 128;  // 16-byte pieces in a wave's staging buffer
+
+template <bool STAGED>
+__global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
+{
+    extern __shared__ u32x4 smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int nchunk = a.nchunk;
+    float* zbuf = reinterpret_cast<float*>(smem + a.rows * nchunk);  // [rows][rpb]
+    u32x4* stage = reinterpret_cast<u32x4*>(zbuf + a.rows * a.rpb) + wave * kMfmaStage;  // STAGED only
+
+    const int j_lo = blockIdx.x * a.rpb;
+    const int j_hi = (j_lo + a.rpb < a.Vd) ? j_lo + a.rpb : a.Vd;
+    const int n_local = j_hi - j_lo;
+    const int ngroups = (n_local + kMfmaGroup - 1) / kMfmaGroup;
+    const int iters = nchunk / (4 * kMfmaUnroll);  // loop iterations per group (32 pieces each)
+
+    const int lrow = lane & 15;
+    const int kg = lane >> 4;
+    const int hrow = lrow < a.rows ? lrow : a.rows - 1;  // columns beyond `rows` repeat the last row
+    const u32x4* hbase = smem + hrow * nchunk;
+    const int hsw = hrow & 15;
+    // staged form: lane l loads piece (l%8) ^ f(row) of row l/8 (+8 for odd loads) of a 128-byte
+    // column block and parks it at position l, so the A read of piece c of row i is at
+    // i*8 + (c ^ f(i)) with f(i) = (i/2)%8: conflict-free on both sides
+    const int ld_row = lane >> 3;
+    const int ld_piece_a = (lane & 7) ^ ((ld_row >> 1) & 7);        // rows 0..7 of the group
+    const int ld_piece_b = (lane & 7) ^ (((ld_row + 8) >> 1) & 7);  // rows 8..15
+    const int a_sw = (lrow >> 1) & 7;
+
+    // position = (group g, iteration it); the loads of the next position are in flight while
+    // the current one is multiplied, also across groups
+    auto load_pos = [&](int gg, int it, u32x4(&buf)[kMfmaUnroll]) {
+        if constexpr (STAGED) {
+            const int jr = j_lo + gg * kMfmaGroup + ld_row;
+            const int ja = jr < j_hi ? jr : j_hi - 1;  // a short last group re-reads the range's last row
+            const int jb = jr + 8 < j_hi ? jr + 8 : j_hi - 1;
+            const u32x4* sa = a.W + (size_t)ja * nchunk + it * (4 * kMfmaUnroll) + ld_piece_a;
+            const u32x4* sb = a.W + (size_t)jb * nchunk + it * (4 * kMfmaUnroll) + ld_piece_b;
+#pragma unroll
+            for (int q = 0; q < kMfmaUnroll / 2; ++q) {
+                buf[2 * q] = __builtin_nontemporal_load(sa + 8 * q);
+                buf[2 * q + 1] = __builtin_nontemporal_load(sb + 8 * q);
+            }
+        } else {
+            int j = j_lo + gg * kMfmaGroup + lrow;
+            j = j < j_hi ? j : j_hi - 1;
+            const u32x4* src = a.W + (size_t)j * nchunk + it * (4 * kMfmaUnroll) + kg;
+#pragma unroll
+            for (int u = 0; u < kMfmaUnroll; ++u)
+                buf[u] = src[4 * u];
+        }
+    };
+    f32x4 acc0 = {0.0f, 0.0f, 0.0f, 0.0f}, acc1 = {0.0f, 0.0f, 0.0f, 0.0f};
+    int g = wave, it = 0;
+    auto step = [&](u32x4(&cur)[kMfmaUnroll], u32x4(&nxt)[kMfmaUnroll]) {
+        int itn = it + 1, gn = g;
+        if (itn == iters) {
+            itn = 0;
+            gn = g + kGemvWaves;
+        }
+        if (gn < ngroups)
+            load_pos(gn, itn, nxt);
+#pragma unroll
+        for (int q = 0; q < kMfmaUnroll / 2; ++q) {
+            const int c0 = it * (4 * kMfmaUnroll) + 8 * q + kg;  // piece of the first 32-wide step
+            u32x4 w0, w1;
+            if constexpr (STAGED) {
+                stage[lane] = cur[2 * q];
+                stage[kWave + lane] = cur[2 * q + 1];
+                __builtin_amdgcn_wave_barrier();  // keep the wave's LDS accesses in program order
+                w0 = stage[lrow * 8 + (kg ^ a_sw)];
+                w1 = stage[lrow * 8 + ((4 + kg) ^ a_sw)];
+                __builtin_amdgcn_wave_barrier();
+            } else {
+                w0 = cur[2 * q];
+                w1 = cur[2 * q + 1];
+            }
+            const u32x4 x0 = hbase[c0 ^ hsw];
+            const u32x4 x1 = hbase[(c0 + 4) ^ hsw];
+            acc0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w0),
+                                                           __builtin_bit_cast(bf16x8, x0), acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w1),
+                                                           __builtin_bit_cast(bf16x8, x1), acc1, 0, 0, 0);
+        }
+        if (it == iters - 1) {
+            const f32x4 z = acc0 + acc1;
+            acc0 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            acc1 = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (lrow < a.rows) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int e = g * kMfmaGroup + 4 * kg + i;
+                    if (e < n_local) {
+                        zbuf[lrow * a.rpb + e] = z[i];
+                        if (a.logits_out != nullptr)
+                            a.logits_out[(size_t)lrow * a.Vd + j_lo + e] = z[i];
+                    }
+                }
+            }
+        }
+        it = itn;
+        g = gn;
+    };
+    u32x4 bufA[kMfmaUnroll], bufB[kMfmaUnroll];
+    if (g < ngroups)
+        load_pos(g, 0, bufA);  // in flight while the hidden states are staged
+
+    for (int x = tid; x < a.rows * nchunk; x += kGemvThreads) {
+        const int r = x / nchunk;
+        const int c = x - r * nchunk;
+        smem[r * nchunk + (c ^ (r & 15))] = a.h[x];
+    }
+    __syncthreads();
+    while (g < ngroups) {
+        step(bufA, bufB);
+        if (g >= ngroups)
+            break;
+        step(bufB, bufA);
+    }
+    __syncthreads();
+    block_tail(a, smem, zbuf, tid, j_lo, n_local);
+}
+
+// LDS bytes of the matrix-core streaming kernel without / with the staging buffers
+static size_t mfma_lds_bytes(int rows, int nchunk, int rpb, bool staged)
+{
+    size_t lds = (size_t)rows * nchunk * sizeof(u32x4) + (size_t)rows * rpb * sizeof(float);
+    if (staged)
+        lds += (size_t)kGemvWaves * kMfmaStage * sizeof(u32x4);
+    return lds;
+}
+
+static hipError_t launch_mfma(const Plan& p, const GemvArgs& ga, hipStream_t s)
+{
+    if (ga.nchunk % (4 * kMfmaUnroll) != 0 || ga.rows > 16)
+        return hipErrorInvalidValue;
+    const bool staged = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, true) <= (size_t)kGemvLdsLimit;
+    size_t lds = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, staged);
+    if (ga.fused) {
+        if (ga.rows > kFusedMaxRows || ga.P > 256 || ga.KP > 16)
+            return hipErrorInvalidValue;
+        const size_t l1 = (size_t)ga.rows * 256 * ((size_t)ga.KP + 1) * 8 + kGemvWaves * sizeof(float2);
+        lds = lds > l1 ? lds : l1;
+    }
+    if (lds > (size_t)kGemvLdsLimit)
+        return hipErrorInvalidValue;
+    auto kern = staged ? gemv_mfma_kernel<true> : gemv_mfma_kernel<false>;
+    static size_t lds_allowed[2] = {48 * 1024, 48 * 1024};  // per variant: raised once, then remembered
+    if (lds > lds_allowed[staged]) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess)
+            return e;
+        lds_allowed[staged] = lds;
+    }
+    hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
+    return hipGetLastError();
+}
+
+template <int NR, int J, bool DOT2>
 static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
     size_t lds = (size_t)NR * ga.nchunk * sizeof(u32x4) + (size_t)NR * ga.rpb * sizeof(float);
@@ -393,6 +584,8 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.out_ids = a.out_ids;
     ga.out_logp = a.out_logp;
     ga.lse_out = a.lse_out;
+    if (p.mfma)
+        return launch_mfma(p, ga, s);
     // rows of W_sub a wave reduces together (J): measured best 1 for a single hidden row, 2 otherwise
     switch (p.NR) {
     case 1: return launch_one<1, 1, true>(p, ga, s);

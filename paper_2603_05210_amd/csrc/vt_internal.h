@@ -27,6 +27,7 @@ struct Plan {
     int J;       // W_sub rows a wave reduces together
     int rpb;     // W_sub rows per workgroup
     int fused;   // the streaming kernel's last workgroup also does the final merge
+    int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
     // GEMM regime
     int tile;    // index into the table of tile shapes
     int n_vtiles, n_rtiles;

@@ -76,6 +76,12 @@ EDGE = [
     (17, 72, 900, 600, 64),       # first row count of the MFMA regime, longest list, K tail
     (2, 64, 150000, 140000, 10),  # more workgroup partials than the fused merge takes
     (9, 128, 150000, 133000, 3),
+    (2, 256, 70000, 65600, 4),    # wide vocabulary, fused merge
+    (2, 256, 150000, 140000, 10),  # the same with more partials than the fused merge takes
+    (5, 256, 70000, 66001, 10),   # matrix-core streaming kernel: ragged last 16-row group and workgroup
+    (9, 256, 131000, 130000, 5),
+    (16, 512, 70000, 69000, 16),
+    (16, 4096, 70000, 65536, 8),  # hidden states leave no LDS for staging: direct-load form
     (129, 64, 700, 257, 16),      # one row and one token past a tile edge
     (256, 128, 2000, 512, 16),    # exact tile multiples
 ]
@@ -111,6 +117,23 @@ def test_exact_arithmetic_cases_are_bit_exact(rows):
     W_dev = to_dev_bf16(Wb)
     d2t_dev = torch.from_numpy(d2t).to(DEV)
     g_ids, g_lp, g_z, g_lse = run_gpu(hb, W_dev, d2t_dev, k)
+    ora = vo.draft_head(hb, Wb, d2t, k)
+    assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
+    assert np.array_equal(g_ids, ora.ids)
+    assert np.max(np.abs(g_lp - ora.logp)) < 1e-3
+
+
+@pytest.mark.parametrize("rows", [5, 11, 16])
+def test_exact_arithmetic_matrix_core_streaming(rows):
+    """The same through the matrix-core streaming kernel (several rows, H % 256 == 0, a
+    vocabulary wide enough for 16-row groups on every wave)."""
+    H, Vd, k = 256, 66003, 12
+    _say("exact (matrix-core streaming) rows=%d" % rows)
+    assert vt.vt_draft_head_regime(rows, H, Vd, k) == 0
+    Wb = synth.small_int_bf16(6, 0, (Vd, H))
+    hb = synth.small_int_bf16(6, 1, (rows, H))
+    d2t = np.arange(Vd, dtype=np.int32)[::-1].copy()
+    g_ids, g_lp, g_z, g_lse = run_gpu(hb, to_dev_bf16(Wb), torch.from_numpy(d2t).to(DEV), k)
     ora = vo.draft_head(hb, Wb, d2t, k)
     assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
     assert np.array_equal(g_ids, ora.ids)
