@@ -35,6 +35,7 @@ STREAM_H = 1
 STREAM_PERM = 2
 STREAM_KEYS = 3
 STREAM_PEAKED = 4
+STREAM_TOKENS = 5
 
 FULL_VOCAB = 128256  # LLaMA-3 vocabulary size (Section 2.3, Table 1)
 
@@ -175,6 +176,28 @@ def zipf_subset(seed: int, V: int, V_draft: int, s: float = 1.1) -> np.ndarray:
     keys = np.log(uniform01(seed, STREAM_KEYS, 0, V)) / w
     chosen_ranks = np.argpartition(-keys, V_draft - 1)[:V_draft]
     return np.sort(perm[chosen_ranks]).astype(np.int32)
+
+
+def zipf_token_stream(seed: int, V: int, n: int, s: float = 1.1, support: int | None = None) -> np.ndarray:
+    """n token ids in [0,V), int32, drawn independently: frequency rank r = 1..support has
+    probability proportional to r**-s and the same seeded permutation as zipf_subset maps
+    ranks to ids (ranks beyond `support` never occur: tokens with zero frequency).  Stands in
+    for the assistant-span token stream of a training corpus (Section 2.2)."""
+    support = V if support is None else support
+    if not 0 < support <= V or n < 0:
+        raise ValueError("need 0 < support <= V and n >= 0")
+    perm = np.argsort(raw_u64(seed, STREAM_PERM, 0, V), kind="stable")
+    w = np.arange(1, support + 1, dtype=np.float64) ** (-s)
+    cdf = np.cumsum(w)
+    cdf /= cdf[-1]
+    out = np.empty(n, dtype=np.int32)
+    step = 1 << 22
+    for a in range(0, n, step):
+        b = min(n, a + step)
+        u = uniform01(seed, STREAM_TOKENS, a, b - a)
+        r = np.minimum(np.searchsorted(cdf, u, side="right"), support - 1)
+        out[a:b] = perm[r]
+    return out
 
 
 def small_int_bf16(seed: int, stream: int, shape, lo: int = -4, hi: int = 4) -> np.ndarray:

@@ -56,3 +56,19 @@ def test_zipf_subset_shape_and_bias():
     assert np.mean(ranks < 2000) > 0.5
     assert np.array_equal(ids, synth.zipf_subset(0, V, 2000))
     assert not np.array_equal(ids, synth.zipf_subset(1, V, 2000))
+
+
+def test_token_stream_is_seeded_in_range_and_heavy_tailed():
+    V, n = 3000, 300_000
+    a = synth.zipf_token_stream(4, V, n)
+    b = synth.zipf_token_stream(4, V, n)
+    assert a.dtype == np.int32 and a.shape == (n,) and np.array_equal(a, b)
+    assert a.min() >= 0 and a.max() < V
+    # a prefix of a longer stream is the shorter stream (counter-based draws)
+    assert np.array_equal(synth.zipf_token_stream(4, V, 1000), a[:1000])
+    f = np.sort(np.bincount(a, minlength=V))[::-1]
+    assert f[0] > 20 * f[V // 10]                    # Zipf(1.1): the head dominates
+    # restricted support: exactly `support` ids can occur
+    c = synth.zipf_token_stream(4, V, n, support=100)
+    assert np.unique(c).size <= 100
+    assert not np.array_equal(synth.zipf_token_stream(5, V, 1000), a[:1000])
