@@ -134,6 +134,57 @@ vt_status vt_draft_head_debug(const uint16_t *h, int64_t rows, int64_t H, const 
 vt_status vt_kernel_timing_enable(int on);
 vt_status vt_kernel_timing_read(int *launches, double *total_ms);
 
+/*
+ * Draft-vocabulary size selection (Section 2, Eq. 1-5).  From a stream of token ids (the
+ * assistant-span tokens of a training corpus, Section 2.2) the call computes, on the device:
+ *   f(v)   the frequency of every token id (freq_out),
+ *   the frequency ranking, most frequent first, equal frequencies by lower id (rank_ids_out:
+ *          its first k entries are the paper's top-k, Section 2.1),
+ *   C(k)   = sum of the k largest frequencies / n_tokens                              (Eq. 2)
+ *   R(k)   = 1 - (F_fixed + 2 d k) / (F_fixed + 2 d V)                                (Eq. 3)
+ *   U(k)   = alpha C(k) + (1 - alpha) R(k)                                            (Eq. 4)
+ *   U~(k)  = U(k) if C(k) >= c_min, else -1                                           (Eq. 5)
+ *   k*     = the k in [k_min, k_max] with the largest U~(k), the smallest such k      (Eq. 1)
+ * and writes the k* selected ids in ascending order to token_ids_out[0..k*), the form
+ * vt_build_subset takes.  The paper searches k with 100 TPE samples (Section 2.5); this call
+ * evaluates every k of the range, which is the maximum that search approximates.  All
+ * floating-point work is IEEE double with one rounding per operation in the order written
+ * above (C = prefix/n; R = 1 - (F + (2d)k) / (F + (2d)V); U = alpha*C + (1-alpha)*R).
+ *
+ *   tokens          device, int32[n_tokens], 16-byte aligned, ids in [0, V)
+ *   n_tokens        1 <= n_tokens < 2^32
+ *   V               1 <= V < 2^27
+ *   d, F_fixed      d >= 1, F_fixed >= 0 (Table 1's fixed components)
+ *   alpha, c_min    0 <= alpha <= 1, 0 <= c_min <= 1
+ *   k_min, k_max    1 <= k_min <= k_max <= V
+ *   freq_out        device, uint32[V]
+ *   rank_ids_out    device, int32[V]
+ *   token_ids_out   device, int32[V] (capacity; the first k* entries are written)
+ *   result          host; filled on VT_OK
+ *   workspace       device, >= vt_select_vocab_workspace_bytes(V) bytes, 16-byte aligned
+ * The call enqueues its kernels on `stream`, waits for them once and then fills *result.
+ * VT_ERR_ID_RANGE: some token id lies outside [0, V) (outputs are then unspecified).
+ * If no k of the range meets the coverage constraint, result->feasible is 0 and k* = k_min.
+ */
+typedef struct {
+    int64_t k_star;
+    int32_t feasible;
+    double C, R, U;      /* Eq. 2, 3, 4 at k* (U is the unpenalised utility) */
+    uint64_t n_tokens;   /* sum of all frequencies */
+} vt_selection;
+
+size_t vt_select_vocab_workspace_bytes(int64_t V);
+
+vt_status vt_validate_select_vocab_args(const void *tokens, int64_t n_tokens, int64_t V, int64_t d, double F_fixed,
+                                        double alpha, double c_min, int64_t k_min, int64_t k_max,
+                                        const void *freq_out, const void *rank_ids_out, const void *token_ids_out,
+                                        const void *result, const void *workspace, size_t workspace_bytes);
+
+vt_status vt_select_vocab(const int32_t *tokens, int64_t n_tokens, int64_t V, int64_t d, double F_fixed,
+                          double alpha, double c_min, int64_t k_min, int64_t k_max, uint32_t *freq_out,
+                          int32_t *rank_ids_out, int32_t *token_ids_out, vt_selection *result, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

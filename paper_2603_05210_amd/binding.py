@@ -27,7 +27,8 @@ EXPORTS = (
     "vt_version", "vt_status_str", "vt_build_subset", "vt_check_token_ids_host",
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
     "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug", "vt_kernel_timing_enable",
-    "vt_kernel_timing_read",
+    "vt_kernel_timing_read", "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
+    "vt_select_vocab",
 )
 
 
@@ -72,6 +73,13 @@ def lib() -> ctypes.CDLL:
         L.vt_kernel_timing_enable.argtypes = [i32]
         L.vt_kernel_timing_read.restype = i32
         L.vt_kernel_timing_read.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+        f64 = ctypes.c_double
+        L.vt_select_vocab_workspace_bytes.restype = sz
+        L.vt_select_vocab_workspace_bytes.argtypes = [i64]
+        L.vt_validate_select_vocab_args.restype = i32
+        L.vt_validate_select_vocab_args.argtypes = [p, i64, i64, i64, f64, f64, f64, i64, i64, p, p, p, p, p, sz]
+        L.vt_select_vocab.restype = i32
+        L.vt_select_vocab.argtypes = [p, i64, i64, i64, f64, f64, f64, i64, i64, p, p, p, p, p, sz, p]
         _lib = L
     return _lib
 
@@ -203,3 +211,33 @@ def vt_kernel_timing_read():
     if st != VT_OK:
         raise VtError(st, "vt_kernel_timing_read")
     return int(n.value), float(ms.value)
+
+
+class VtSelection(ctypes.Structure):
+    """Mirror of vt_selection in include/vt.h."""
+    _fields_ = [("k_star", ctypes.c_int64), ("feasible", ctypes.c_int32), ("C", ctypes.c_double),
+                ("R", ctypes.c_double), ("U", ctypes.c_double), ("n_tokens", ctypes.c_uint64)]
+
+
+def vt_select_vocab_workspace_bytes(V: int) -> int:
+    return int(lib().vt_select_vocab_workspace_bytes(V))
+
+
+def vt_select_vocab(tokens: torch.Tensor, V: int, d: int, F_fixed: float, alpha: float, c_min: float,
+                    k_min: int, k_max: int, workspace: torch.Tensor | None = None):
+    """Vocabulary-size selection over a device stream of token ids.  Returns (selection, freq[V]
+    as int32 bit patterns of the uint32 counts, rank_ids[V], token_ids[k*]) -- device tensors."""
+    _devi32(tokens, "tokens")
+    dev = tokens.device
+    freq = torch.empty(V, dtype=torch.int32, device=dev)
+    rank_ids = torch.empty(V, dtype=torch.int32, device=dev)
+    token_ids = torch.empty(V, dtype=torch.int32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(16, vt_select_vocab_workspace_bytes(V)), dtype=torch.uint8, device=dev)
+    res = VtSelection()
+    st = lib().vt_select_vocab(tokens.data_ptr(), tokens.numel(), V, d, float(F_fixed), float(alpha), float(c_min),
+                               k_min, k_max, freq.data_ptr(), rank_ids.data_ptr(), token_ids.data_ptr(),
+                               ctypes.addressof(res), workspace.data_ptr(), workspace.numel(), _stream_ptr(tokens))
+    if st != VT_OK:
+        raise VtError(st, "vt_select_vocab")
+    return res, freq, rank_ids, token_ids[: int(res.k_star)]

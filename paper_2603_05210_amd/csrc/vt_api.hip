@@ -9,6 +9,7 @@
 #include <vector>
 
 #include "vt_internal.h"
+#include "vt_select.h"
 
 namespace vt {
 
@@ -305,6 +306,67 @@ vt_status vt_kernel_timing_read(int* launches, double* total_ms)
     *launches = n;
     *total_ms = total;
     g_timing.used = 0;
+    return VT_OK;
+}
+
+size_t vt_select_vocab_workspace_bytes(int64_t V)
+{
+    if (V < 1 || V >= ((int64_t)1 << 27))
+        return 0;
+    return vt::select_layout(V).total;
+}
+
+vt_status vt_validate_select_vocab_args(const void* tokens, int64_t n_tokens, int64_t V, int64_t d, double F_fixed,
+                                        double alpha, double c_min, int64_t k_min, int64_t k_max, const void* freq_out,
+                                        const void* rank_ids_out, const void* token_ids_out, const void* result,
+                                        const void* workspace, size_t workspace_bytes)
+{
+    if (!tokens || !freq_out || !rank_ids_out || !token_ids_out || !result)
+        return VT_ERR_NULL;
+    if (V < 1 || V >= ((int64_t)1 << 27) || n_tokens < 1 || n_tokens >= ((int64_t)1 << 32) || d < 1 ||
+        !(F_fixed >= 0.0) || !(alpha >= 0.0 && alpha <= 1.0) || !(c_min >= 0.0 && c_min <= 1.0))
+        return VT_ERR_SHAPE;
+    if (k_min < 1 || k_min > k_max || k_max > V)
+        return VT_ERR_K;
+    if (!workspace || workspace_bytes < vt_select_vocab_workspace_bytes(V))
+        return VT_ERR_WORKSPACE;
+    if (!aligned16(tokens) || !aligned16(workspace) || (reinterpret_cast<uintptr_t>(freq_out) & 3u) ||
+        (reinterpret_cast<uintptr_t>(rank_ids_out) & 3u) || (reinterpret_cast<uintptr_t>(token_ids_out) & 3u))
+        return VT_ERR_ALIGN;
+    return VT_OK;
+}
+
+vt_status vt_select_vocab(const int32_t* tokens, int64_t n_tokens, int64_t V, int64_t d, double F_fixed, double alpha,
+                          double c_min, int64_t k_min, int64_t k_max, uint32_t* freq_out, int32_t* rank_ids_out,
+                          int32_t* token_ids_out, vt_selection* result, void* workspace, size_t workspace_bytes,
+                          void* stream)
+{
+    const vt_status st = vt_validate_select_vocab_args(tokens, n_tokens, V, d, F_fixed, alpha, c_min, k_min, k_max,
+                                                       freq_out, rank_ids_out, token_ids_out, result, workspace,
+                                                       workspace_bytes);
+    if (st != VT_OK)
+        return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const vt::SelectLayout L = vt::select_layout(V);
+    vt::SelectParams prm;
+    prm.d = d;
+    prm.F_fixed = F_fixed;
+    prm.alpha = alpha;
+    prm.c_min = c_min;
+    prm.k_min = k_min;
+    prm.k_max = k_max;
+    char* ws = static_cast<char*>(workspace);
+    if (vt::launch_select(tokens, n_tokens, (int)V, prm, freq_out, rank_ids_out, token_ids_out, ws, L, s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    int err = 0;
+    vt_selection res;
+    if (hipMemcpyAsync(&err, ws + L.off_err, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(&res, ws + L.off_result, sizeof(res), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    if (err != 0)
+        return VT_ERR_ID_RANGE;
+    *result = res;
     return VT_OK;
 }
 

@@ -107,3 +107,23 @@ def test_regime_and_workspace_query(rows, H, Vd, k, regime):
 
 def test_timing_read_rejects_null():
     assert vt.lib().vt_kernel_timing_read(None, None) == 1
+
+
+def test_select_vocab_argument_validation():
+    f = vt.lib().vt_validate_select_vocab_args
+    V = 128256
+    wsb = vt.vt_select_vocab_workspace_bytes(V)
+    assert wsb >= (1 << 17) * 8 + V * 4
+    assert vt.vt_select_vocab_workspace_bytes(0) == 0
+
+    def call(tokens=FAKE, n=1000, V=V, d=4096, F=5.872e8, alpha=0.5, c_min=0.9, k_min=1024, k_max=V,
+             freq=FAKE, rank=FAKE, ids=FAKE, res=FAKE, ws=FAKE, wsb=wsb):
+        return f(tokens, n, V, d, F, alpha, c_min, k_min, k_max, freq, rank, ids, res, ws, wsb)
+
+    assert call() == 0
+    assert call(tokens=None) == 1 and call(res=None) == 1 and call(ids=None) == 1
+    assert call(n=0) == 2 and call(n=1 << 32) == 2 and call(d=0) == 2
+    assert call(alpha=1.5) == 2 and call(alpha=float("nan")) == 2 and call(c_min=-0.1) == 2 and call(F=-1.0) == 2
+    assert call(k_min=0) == 3 and call(k_min=2000, k_max=1999) == 3 and call(k_max=V + 1) == 3
+    assert call(ws=None) == 6 and call(wsb=wsb - 1) == 6
+    assert call(tokens=FAKE + 4) == 7 and call(freq=FAKE + 2) == 7
