@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE profiler counters)")
+    ap.add_argument("--select", action="store_true",
+                    help="measure only the vocabulary-size selection call and exit")
     ap.add_argument("--shape", type=str, default=None,
                     help="rows,H,V_draft,k: run this shape as the headline instead (exploration)")
     return ap.parse_args()
@@ -220,6 +222,39 @@ def calibrate_copy():
     print(json.dumps({"calibrate_copy_bytes": n, "reads": n, "writes": n, "launches": 5}))
 
 
+def selector_bench(torch, vt, synth, dev, with_cpu, n_tokens=32 * 1024 * 1024, calls=5):
+    """The vocabulary-size selection (Eq. 1-5) on a Zipf(1.1) stream over LLaMA-3's vocabulary
+    with Table 1's constants: whole-call time (kernels + the call's one synchronisation)."""
+    V, d = synth.FULL_VOCAB, 4096
+    F_fixed = (100.7 + 436.2 + 50.3) * 1e6
+    alpha, c_min, k_min = 0.5, 0.9, 1024
+    tokens = synth.zipf_token_stream(0, V, n_tokens)
+    t_dev = torch.from_numpy(tokens).to(dev)
+    ws = torch.empty(vt.vt_select_vocab_workspace_bytes(V), dtype=torch.uint8, device=dev)
+    res = None
+    for _ in range(2):
+        res, _, _, _ = vt.vt_select_vocab(t_dev, V, d, F_fixed, alpha, c_min, k_min, V, workspace=ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        res, _, _, _ = vt.vt_select_vocab(t_dev, V, d, F_fixed, alpha, c_min, k_min, V, workspace=ws)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / calls
+    out = dict(workload="select_vocab: V=%d d=%d n_tokens=%d Zipf(1.1) alpha=%g c_min=%g" % (V, d, n_tokens, alpha, c_min),
+               ms_per_call=ms, Mtokens_per_s=n_tokens / ms / 1e3, stream_GBps=4.0 * n_tokens / (ms * 1e-3) / 1e9,
+               k_star=int(res.k_star), C=res.C, R=res.R, U=res.U)
+    if with_cpu:
+        from oracle import vs_oracle as vs
+        sample = tokens[: 8 * 1024 * 1024]
+        t0 = time.perf_counter()
+        ora = vs.select_vocab(sample, V, d, F_fixed, alpha, c_min, k_min, V)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = dict(value=sample.size / dt / 1e6, unit="Mtokens/s", cores=1, kind="oracle",
+                                   sample="first %d tokens of the same stream, one call" % sample.size,
+                                   k_star=ora.k_star)
+    return out
+
+
 def main():
     args = parse_args()
     if args.calibrate_copy:
@@ -241,6 +276,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.select:
+        print(json.dumps({"selector": selector_bench(torch, vt, synth, dev, with_cpu=not args.no_cpu)}))
+        return
     runner = Runner(torch, vt, synth, dev)
 
     wl = workloads()
@@ -269,6 +307,10 @@ def main():
             del s
             torch.cuda.empty_cache()
 
+    selector = None
+    if not args.no_sweep and not args.only:
+        selector = selector_bench(torch, vt, synth, dev, with_cpu=not args.no_cpu)
+
     out = {
         "metric": "draft_lm_head_us_per_step",
         "value": head_rep["us_per_step"],
@@ -289,6 +331,7 @@ def main():
         "roofline": head_rep["roofline"],
         "cpu_baseline": cpu,
         "sweep": sweep,
+        "selector": selector,
     }
     print(json.dumps(out))
 

@@ -25,31 +25,38 @@ namespace vt {
 // addresses.  Each workgroup keeps an open-addressed table of kHistSlots (id, count) pairs in
 // LDS: a token whose slot is free or already its own is counted there, the rest go to memory;
 // the table is flushed once at the end.
-constexpr int kHistThreads = 256;
-constexpr int kHistSlots = 8192;
+constexpr int kHistThreads = 1024;
+constexpr int kHistSlots = 16384;  // 128 KiB of LDS: one workgroup per compute unit
 constexpr int kHistEmpty = -1;
 
 __global__ void __launch_bounds__(kHistThreads) hist_kernel(const int32_t* __restrict__ tokens, int64_t n, int V,
                                                             uint32_t* __restrict__ freq, int* __restrict__ err)
 {
-    __shared__ int tab_id[kHistSlots];
-    __shared__ uint32_t tab_cnt[kHistSlots];
+    extern __shared__ int hist_lds[];
+    int* tab_id = hist_lds;
+    uint32_t* tab_cnt = reinterpret_cast<uint32_t*>(hist_lds + kHistSlots);
     for (int i = threadIdx.x; i < kHistSlots; i += kHistThreads) {
         tab_id[i] = kHistEmpty;
         tab_cnt[i] = 0u;
     }
     __syncthreads();
+    // claim-or-match at a slot: true when the token may be counted there
+    auto try_slot = [&](int slot, int t) {
+        int owner = tab_id[slot];
+        if (owner == kHistEmpty)
+            owner = atomicCAS(&tab_id[slot], kHistEmpty, t);
+        return owner == kHistEmpty || owner == t;
+    };
     auto count = [&](int t) {
         if (t < 0 || t >= V) {
             atomicOr(err, 1);
             return;
         }
-        const int slot = (int)(((uint32_t)t * 2654435761u) >> 19);  // top 13 bits of a multiplicative hash
-        int owner = tab_id[slot];
-        if (owner == kHistEmpty)
-            owner = atomicCAS(&tab_id[slot], kHistEmpty, t);
-        if (owner == kHistEmpty || owner == t)
+        const int slot = (int)(((uint32_t)t * 2654435761u) >> 18);  // top 14 bits of a multiplicative hash
+        if (try_slot(slot, t))
             atomicAdd(&tab_cnt[slot], 1u);
+        else if (try_slot(slot ^ 1, t))
+            atomicAdd(&tab_cnt[slot ^ 1], 1u);
         else
             atomicAdd(&freq[t], 1u);
     };
@@ -167,60 +174,107 @@ __device__ __forceinline__ bool beats(const Best& a, const Best& b)  // larger u
     return a.u > b.u || (a.u == b.u && a.k < b.k);
 }
 
-// One workgroup.  Thread t owns the ranks [t*per, (t+1)*per): sums their frequencies, an
-// exclusive scan over the 1024 sums gives its starting prefix, a second walk evaluates Eq. 2-5
-// at every k of the range and keeps the best.
+// One workgroup of 16 waves.  Wave w owns a contiguous segment of ranks and walks it in tiles of
+// 64 (lane = rank within the tile: coalesced 512-byte loads).  Pass 1 sums the segment's
+// frequencies and writes the ranking; the 16 sums give every wave its starting prefix; pass 2
+// scans each tile across the lanes, evaluates Eq. 2-5 at every k of the range and keeps the best.
+constexpr int kScanWaves = kScanThreads / 64;
+
+__device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long x, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long y = __shfl_up(x, off, 64);
+        if (lane >= off)
+            x += y;
+    }
+    return x;
+}
+
 __global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* __restrict__ keys, int V, SelectParams prm,
                                                                int32_t* __restrict__ rank_ids, vt_selection* __restrict__ out)
 {
 #pragma clang fp contract(off)
-    __shared__ unsigned long long part[kScanThreads];
+    __shared__ unsigned long long wsum[kScanWaves];
     __shared__ Best best_s[kScanThreads];
     __shared__ int feas_s;
     const int t = threadIdx.x;
-    const int per = (V + kScanThreads - 1) / kScanThreads;
-    const int r0 = t * per < V ? t * per : V;
-    const int r1 = r0 + per < V ? r0 + per : V;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const int seg = ((V + kScanWaves - 1) / kScanWaves + 63) & ~63;  // ranks per wave, whole tiles
+    const int r0 = wave * seg < V ? wave * seg : V;
+    const int r1 = r0 + seg < V ? r0 + seg : V;
     if (t == 0)
         feas_s = 0;
-    unsigned long long sum = 0;
-    for (int r = r0; r < r1; ++r) {
-        const uint64_t key = keys[r];
-        sum += key >> 32;
-        rank_ids[r] = (int32_t)(0xFFFFFFFFu - (uint32_t)key);
+
+    constexpr int TB = 8;  // tiles fetched together: the loop is bound by load latency otherwise
+    unsigned long long lsum = 0;
+    for (int rb = r0; rb < r1; rb += 64 * TB) {
+        uint64_t kb[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int r = rb + 64 * u + lane;
+            kb[u] = r < r1 ? keys[r] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int r = rb + 64 * u + lane;
+            if (r < r1) {
+                lsum += kb[u] >> 32;
+                rank_ids[r] = (int32_t)(0xFFFFFFFFu - (uint32_t)kb[u]);
+            }
+        }
     }
-    part[t] = sum;
+    const unsigned long long wtot = __shfl(wave_incl_scan_u64(lsum, lane), 63, 64);
+    if (lane == 0)
+        wsum[wave] = wtot;
     __syncthreads();
-    // exclusive scan, Hillis-Steele over 1024 values (10 rounds)
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        const unsigned long long add = t >= off ? part[t - off] : 0ull;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
+    unsigned long long carry = 0, total = 0;
+    for (int w = 0; w < kScanWaves; ++w) {
+        const unsigned long long x = wsum[w];
+        carry += w < wave ? x : 0ull;
+        total += x;
     }
-    unsigned long long prefix = part[t] - sum;
-    const unsigned long long total = part[kScanThreads - 1];
 
     const double tot = (double)total;
     const double two_d = 2.0 * (double)prm.d;
     const double den = prm.F_fixed + two_d * (double)V;
     const double one_minus_alpha = 1.0 - prm.alpha;
     Best best = {-2.0, (long long)V + 1};  // below every penalised utility
+    double best_C = 0.0, best_R = 0.0, best_U = 0.0;
     bool feas = false;
-    for (int r = r0; r < r1; ++r) {
-        prefix += keys[r] >> 32;
+    for (int rb0 = r0; rb0 < r1; rb0 += 64 * TB) {
+        uint64_t kb[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int r = rb0 + 64 * u + lane;
+            kb[u] = r < r1 ? keys[r] : 0ull;
+        }
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+        const int r = rb0 + 64 * u + lane;
+        const unsigned long long cnt = kb[u] >> 32;
+        const unsigned long long incl = wave_incl_scan_u64(cnt, lane);
+        const unsigned long long prefix = carry + incl;  // sum of the r+1 largest frequencies
+        carry += __shfl(incl, 63, 64);
         const long long k = (long long)r + 1;
-        if (k < prm.k_min || k > prm.k_max)
-            continue;
-        const double C = (double)prefix / tot;
-        const double num = prm.F_fixed + two_d * (double)k;
-        const double R = 1.0 - num / den;
-        const double U = prm.alpha * C + one_minus_alpha * R;
-        const bool ok = C >= prm.c_min;
-        feas |= ok;
-        const Best cand = {ok ? U : -1.0, k};
-        if (beats(cand, best))
-            best = cand;
+        if (r < r1 && k >= prm.k_min && k <= prm.k_max) {
+            const double C = (double)prefix / tot;
+            const double num = prm.F_fixed + two_d * (double)k;
+            const double R = 1.0 - num / den;
+            const double U = prm.alpha * C + one_minus_alpha * R;
+            const bool ok = C >= prm.c_min;
+            feas |= ok;
+            const Best cand = {ok ? U : -1.0, k};
+            if (beats(cand, best)) {
+                best = cand;
+                // C, R, U at the best k so far travel with it (reported below)
+                best_C = C;
+                best_R = R;
+                best_U = U;
+            }
+        }
+        }
     }
     if (feas)
         atomicOr(&feas_s, 1);
@@ -231,20 +285,13 @@ __global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* _
             best_s[t] = best_s[t + off];
         __syncthreads();
     }
-    // the thread that owns rank k*-1 reports C, R, U there
-    const long long ks = best_s[0].k;
-    if (ks - 1 >= r0 && ks - 1 < r1) {
-        unsigned long long pre = part[t] - sum;
-        for (int r = r0; r < (int)ks; ++r)
-            pre += keys[r] >> 32;
-        const double C = (double)pre / tot;
-        const double num = prm.F_fixed + two_d * (double)ks;
-        const double R = 1.0 - num / den;
-        out->k_star = ks;
+    // the thread whose own best is the overall best reports (k is unique to one thread)
+    if (best.k == best_s[0].k) {
+        out->k_star = best.k;
         out->feasible = feas_s;
-        out->C = C;
-        out->R = R;
-        out->U = prm.alpha * C + one_minus_alpha * R;
+        out->C = best_C;
+        out->R = best_R;
+        out->U = best_U;
         out->n_tokens = total;
     }
 }
@@ -258,29 +305,53 @@ __global__ void mark_kernel(const int32_t* __restrict__ rank_ids, const vt_selec
         mark[rank_ids[r]] = (r < sel->k_star) ? 1u : 0u;
 }
 
+// One workgroup; wave w owns a contiguous segment of ids, tiles of 64: a ballot of the marks
+// gives both the tile's count and every marked lane's position.
 __global__ void __launch_bounds__(kScanThreads) compact_kernel(const uint32_t* __restrict__ mark, int V,
                                                                int32_t* __restrict__ token_ids)
 {
-    __shared__ unsigned int part[kScanThreads];
+    __shared__ unsigned int wcnt[kScanWaves];
     const int t = threadIdx.x;
-    const int per = (V + kScanThreads - 1) / kScanThreads;
-    const int v0 = t * per < V ? t * per : V;
-    const int v1 = v0 + per < V ? v0 + per : V;
+    const int lane = t & 63;
+    const int wave = t >> 6;
+    const int seg = ((V + kScanWaves - 1) / kScanWaves + 63) & ~63;
+    const int v0 = wave * seg < V ? wave * seg : V;
+    const int v1 = v0 + seg < V ? v0 + seg : V;
+    constexpr int TB = 8;  // tiles fetched together
     unsigned int cnt = 0;
-    for (int v = v0; v < v1; ++v)
-        cnt += mark[v];
-    part[t] = cnt;
-    __syncthreads();
-    for (int off = 1; off < kScanThreads; off <<= 1) {
-        const unsigned int add = t >= off ? part[t - off] : 0u;
-        __syncthreads();
-        part[t] += add;
-        __syncthreads();
+    for (int vb = v0; vb < v1; vb += 64 * TB) {
+        uint32_t mb[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int v = vb + 64 * u + lane;
+            mb[u] = v < v1 ? mark[v] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < TB; ++u)
+            cnt += (unsigned int)__popcll(__ballot(mb[u] != 0u));
     }
-    unsigned int pos = part[t] - cnt;
-    for (int v = v0; v < v1; ++v)
-        if (mark[v])
-            token_ids[pos++] = v;
+    if (lane == 0)
+        wcnt[wave] = cnt;
+    __syncthreads();
+    unsigned int pos = 0;
+    for (int w = 0; w < wave; ++w)
+        pos += wcnt[w];
+    for (int vb = v0; vb < v1; vb += 64 * TB) {
+        uint32_t mb[TB];
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const int v = vb + 64 * u + lane;
+            mb[u] = v < v1 ? mark[v] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const bool m = mb[u] != 0u;
+            const unsigned long long b = __ballot(m);
+            if (m)
+                token_ids[pos + (unsigned int)__popcll(b & ((1ull << lane) - 1ull))] = vb + 64 * u + lane;
+            pos += (unsigned int)__popcll(b);
+        }
+    }
 }
 
 // ------------------------------------------------------------------ host side
@@ -319,11 +390,20 @@ hipError_t launch_select(const int32_t* tokens, int64_t n, int V, const SelectPa
     e = hipMemsetAsync(err, 0, sizeof(int), s);
     if (e != hipSuccess)
         return e;
-    // two workgroups per compute unit (64 KiB of LDS each), fewer for short streams
+    // one workgroup per compute unit (128 KiB of LDS each), fewer for short streams
+    constexpr size_t hist_lds = (size_t)kHistSlots * 8;
+    static bool lds_raised = false;
+    if (!lds_raised) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void*>(hist_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)hist_lds);
+        if (e != hipSuccess)
+            return e;
+        lds_raised = true;
+    }
     int64_t hb = (n + (int64_t)kHistThreads * 64 - 1) / ((int64_t)kHistThreads * 64);
-    if (hb > 512)
-        hb = 512;
-    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)hb), dim3(kHistThreads), 0, s, tokens, n, V, freq, err);
+    if (hb > 256)
+        hb = 256;
+    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)hb), dim3(kHistThreads), hist_lds, s, tokens, n, V, freq, err);
 
     hipLaunchKernelGGL(make_keys_kernel, dim3((L.N2 + 255) / 256), dim3(256), 0, s, freq, V, L.N2, keys);
     const int chunks = L.N2 / kSortChunk;
