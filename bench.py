@@ -243,6 +243,20 @@ def selector_bench(torch, vt, synth, dev, with_cpu, n_tokens=32 * 1024 * 1024, c
     out = dict(workload="select_vocab: V=%d d=%d n_tokens=%d Zipf(1.1) alpha=%g c_min=%g" % (V, d, n_tokens, alpha, c_min),
                ms_per_call=ms, Mtokens_per_s=n_tokens / ms / 1e3, stream_GBps=4.0 * n_tokens / (ms * 1e-3) / 1e9,
                k_star=int(res.k_star), C=res.C, R=res.R, U=res.U)
+    # coverage of the selected vocabulary on the same stream (Table 4's two ratios)
+    _, _, _, ids = vt.vt_select_vocab(t_dev, V, d, F_fixed, alpha, c_min, k_min, V, workspace=ws)
+    t2d = vt.vt_build_t2d(ids.contiguous(), V)
+    cws = torch.empty(vt.vt_coverage_workspace_bytes(V), dtype=torch.uint8, device=dev)
+    cov, _ = vt.vt_coverage(t_dev, t2d, workspace=cws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(calls):
+        cov, _ = vt.vt_coverage(t_dev, t2d, workspace=cws)
+    torch.cuda.synchronize()
+    cms = (time.perf_counter() - t0) * 1e3 / calls
+    out["coverage"] = dict(ms_per_call=cms, Mtokens_per_s=n_tokens / cms / 1e3,
+                           stream_GBps=4.0 * n_tokens / (cms * 1e-3) / 1e9, freq_coverage=cov.freq_coverage,
+                           unique_coverage=cov.unique_coverage)
     if with_cpu:
         from oracle import vs_oracle as vs
         sample = tokens[: 8 * 1024 * 1024]

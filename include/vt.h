@@ -185,6 +185,49 @@ vt_status vt_select_vocab(const int32_t *tokens, int64_t n_tokens, int64_t V, in
                           int32_t *rank_ids_out, int32_t *token_ids_out, vt_selection *result, void *workspace,
                           size_t workspace_bytes, void *stream);
 
+/*
+ * Target-to-draft index buffer (Section 1: the t2d / d2t buffers of a draft with a reduced
+ * vocabulary).  t2d_out[v] = j where d2t[j] = v, and -1 for every target id outside V_d.
+ *
+ *   d2t        device, int32[V_draft], distinct ids in [0, V)  (vt_build_subset's d2t_out)
+ *   t2d_out    device, int32[V]
+ *   workspace  device, >= vt_coverage_workspace_bytes(V) bytes, 16-byte aligned
+ * The call waits for its kernels once so that VT_ERR_ID_RANGE / VT_ERR_ID_DUP can be
+ * returned (t2d_out is then unspecified).
+ */
+vt_status vt_build_t2d(const int32_t *d2t, int64_t V_draft, int64_t V, int32_t *t2d_out, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+/*
+ * Coverage of a draft vocabulary on a stream of token ids (Section 2.2, Eq. 2 evaluated on the
+ * stream; Section 5.1, Table 4): the share of token occurrences whose token has a draft index
+ * ("Freq. Cov.") and the share of distinct tokens of the stream that have one ("Unique Cov.").
+ * Counts of several streams add up (Table 4's combined row).  Optionally writes the stream
+ * mapped through t2d (-1 where the target token has no draft index), the remapping that masks
+ * out-of-vocabulary targets.
+ *
+ *   tokens          device, int32[n_tokens], ids in [0, V); 1 <= n_tokens
+ *   t2d             device, int32[V]  (vt_build_t2d)
+ *   draft_ids_out   device, int32[n_tokens], or NULL
+ *   result          host; filled on VT_OK
+ *   workspace       device, >= vt_coverage_workspace_bytes(V) bytes, 16-byte aligned
+ * The call waits for its kernels once.  VT_ERR_ID_RANGE: a token id outside [0, V).
+ */
+typedef struct {
+    uint64_t n_tokens;          /* occurrences                                   */
+    uint64_t n_covered;         /* occurrences whose token is in V_d             */
+    uint64_t n_unique;          /* distinct tokens in the stream                 */
+    uint64_t n_unique_covered;  /* distinct tokens in the stream that are in V_d */
+    double freq_coverage;       /* n_covered / n_tokens                          */
+    double unique_coverage;     /* n_unique_covered / n_unique                   */
+} vt_coverage_result;
+
+size_t vt_coverage_workspace_bytes(int64_t V);
+
+vt_status vt_coverage(const int32_t *tokens, int64_t n_tokens, const int32_t *t2d, int64_t V,
+                      int32_t *draft_ids_out, vt_coverage_result *result, void *workspace,
+                      size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -28,7 +28,7 @@ EXPORTS = (
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
     "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug", "vt_kernel_timing_enable",
     "vt_kernel_timing_read", "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
-    "vt_select_vocab",
+    "vt_select_vocab", "vt_build_t2d", "vt_coverage_workspace_bytes", "vt_coverage",
 )
 
 
@@ -80,6 +80,12 @@ def lib() -> ctypes.CDLL:
         L.vt_validate_select_vocab_args.argtypes = [p, i64, i64, i64, f64, f64, f64, i64, i64, p, p, p, p, p, sz]
         L.vt_select_vocab.restype = i32
         L.vt_select_vocab.argtypes = [p, i64, i64, i64, f64, f64, f64, i64, i64, p, p, p, p, p, sz, p]
+        L.vt_coverage_workspace_bytes.restype = sz
+        L.vt_coverage_workspace_bytes.argtypes = [i64]
+        L.vt_build_t2d.restype = i32
+        L.vt_build_t2d.argtypes = [p, i64, i64, p, p, sz, p]
+        L.vt_coverage.restype = i32
+        L.vt_coverage.argtypes = [p, i64, p, i64, p, p, p, sz, p]
         _lib = L
     return _lib
 
@@ -241,3 +247,46 @@ def vt_select_vocab(tokens: torch.Tensor, V: int, d: int, F_fixed: float, alpha:
     if st != VT_OK:
         raise VtError(st, "vt_select_vocab")
     return res, freq, rank_ids, token_ids[: int(res.k_star)]
+
+
+class VtCoverage(ctypes.Structure):
+    """Mirror of vt_coverage_result in include/vt.h."""
+    _fields_ = [("n_tokens", ctypes.c_uint64), ("n_covered", ctypes.c_uint64), ("n_unique", ctypes.c_uint64),
+                ("n_unique_covered", ctypes.c_uint64), ("freq_coverage", ctypes.c_double),
+                ("unique_coverage", ctypes.c_double)]
+
+
+def vt_coverage_workspace_bytes(V: int) -> int:
+    return int(lib().vt_coverage_workspace_bytes(V))
+
+
+def vt_build_t2d(d2t: torch.Tensor, V: int, workspace: torch.Tensor | None = None) -> torch.Tensor:
+    """t2d[V] (device int32) from the draft-to-target buffer d2t[V_draft]."""
+    _devi32(d2t, "d2t")
+    t2d = torch.empty(V, dtype=torch.int32, device=d2t.device)
+    if workspace is None:
+        workspace = torch.empty(max(16, vt_coverage_workspace_bytes(V)), dtype=torch.uint8, device=d2t.device)
+    st = lib().vt_build_t2d(d2t.data_ptr(), d2t.numel(), V, t2d.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                            _stream_ptr(d2t))
+    if st != VT_OK:
+        raise VtError(st, "vt_build_t2d")
+    return t2d
+
+
+def vt_coverage(tokens: torch.Tensor, t2d: torch.Tensor, want_draft_ids: bool = False,
+                workspace: torch.Tensor | None = None):
+    """Coverage counts and ratios of the vocabulary behind t2d on a device token stream; with
+    want_draft_ids also the stream mapped through t2d.  Returns (VtCoverage, draft_ids or None)."""
+    _devi32(tokens, "tokens")
+    _devi32(t2d, "t2d")
+    V = t2d.numel()
+    if workspace is None:
+        workspace = torch.empty(max(16, vt_coverage_workspace_bytes(V)), dtype=torch.uint8, device=tokens.device)
+    out = torch.empty(tokens.numel(), dtype=torch.int32, device=tokens.device) if want_draft_ids else None
+    res = VtCoverage()
+    st = lib().vt_coverage(tokens.data_ptr(), tokens.numel(), t2d.data_ptr(), V,
+                           out.data_ptr() if out is not None else None, ctypes.addressof(res),
+                           workspace.data_ptr(), workspace.numel(), _stream_ptr(tokens))
+    if st != VT_OK:
+        raise VtError(st, "vt_coverage")
+    return res, out

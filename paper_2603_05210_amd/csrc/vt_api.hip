@@ -10,6 +10,7 @@
 
 #include "vt_internal.h"
 #include "vt_select.h"
+#include "vt_coverage.h"
 
 namespace vt {
 
@@ -367,6 +368,74 @@ vt_status vt_select_vocab(const int32_t* tokens, int64_t n_tokens, int64_t V, in
     if (err != 0)
         return VT_ERR_ID_RANGE;
     *result = res;
+    return VT_OK;
+}
+
+size_t vt_coverage_workspace_bytes(int64_t V)
+{
+    if (V < 1 || V >= ((int64_t)1 << 31))
+        return 0;
+    return vt::coverage_layout(V).total;
+}
+
+vt_status vt_build_t2d(const int32_t* d2t, int64_t V_draft, int64_t V, int32_t* t2d_out, void* workspace,
+                       size_t workspace_bytes, void* stream)
+{
+    if (!d2t || !t2d_out)
+        return VT_ERR_NULL;
+    if (V < 1 || V >= ((int64_t)1 << 31) || V_draft < 1 || V_draft > V)
+        return VT_ERR_SHAPE;
+    if (!workspace || workspace_bytes < vt_coverage_workspace_bytes(V))
+        return VT_ERR_WORKSPACE;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(d2t) & 3u) || (reinterpret_cast<uintptr_t>(t2d_out) & 3u))
+        return VT_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const vt::CoverageLayout L = vt::coverage_layout(V);
+    int* err_dev = reinterpret_cast<int*>(static_cast<char*>(workspace) + L.off_err);
+    if (vt::launch_build_t2d(d2t, (int)V_draft, (int)V, t2d_out, err_dev, s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    int err = 0;
+    if (hipMemcpyAsync(&err, err_dev, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    if (err & 1)
+        return VT_ERR_ID_RANGE;
+    if (err & 2)
+        return VT_ERR_ID_DUP;
+    return VT_OK;
+}
+
+vt_status vt_coverage(const int32_t* tokens, int64_t n_tokens, const int32_t* t2d, int64_t V, int32_t* draft_ids_out,
+                      vt_coverage_result* result, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!tokens || !t2d || !result)
+        return VT_ERR_NULL;
+    if (V < 1 || V >= ((int64_t)1 << 31) || n_tokens < 1)
+        return VT_ERR_SHAPE;
+    if (!workspace || workspace_bytes < vt_coverage_workspace_bytes(V))
+        return VT_ERR_WORKSPACE;
+    if (!aligned16(workspace) || (reinterpret_cast<uintptr_t>(tokens) & 3u) || (reinterpret_cast<uintptr_t>(t2d) & 3u) ||
+        (reinterpret_cast<uintptr_t>(draft_ids_out) & 3u))
+        return VT_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const vt::CoverageLayout L = vt::coverage_layout(V);
+    char* ws = static_cast<char*>(workspace);
+    if (vt::launch_coverage(tokens, n_tokens, t2d, (int)V, draft_ids_out, ws, L, s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    int err = 0;
+    unsigned long long counters[3] = {0, 0, 0};
+    if (hipMemcpyAsync(&err, ws + L.off_err, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipMemcpyAsync(counters, ws + L.off_counters, sizeof(counters), hipMemcpyDeviceToHost, s) != hipSuccess ||
+        hipStreamSynchronize(s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    if (err != 0)
+        return VT_ERR_ID_RANGE;
+    result->n_tokens = (uint64_t)n_tokens;
+    result->n_covered = counters[0];
+    result->n_unique = counters[1];
+    result->n_unique_covered = counters[2];
+    result->freq_coverage = (double)counters[0] / (double)n_tokens;
+    result->unique_coverage = (double)counters[2] / (double)counters[1];
     return VT_OK;
 }
 

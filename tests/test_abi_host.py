@@ -127,3 +127,21 @@ def test_select_vocab_argument_validation():
     assert call(k_min=0) == 3 and call(k_min=2000, k_max=1999) == 3 and call(k_max=V + 1) == 3
     assert call(ws=None) == 6 and call(wsb=wsb - 1) == 6
     assert call(tokens=FAKE + 4) == 7 and call(freq=FAKE + 2) == 7
+
+
+def test_coverage_argument_validation():
+    L = vt.lib()
+    V = 128256
+    wsb = vt.vt_coverage_workspace_bytes(V)
+    assert wsb >= (V + 31) // 32 * 4 and vt.vt_coverage_workspace_bytes(0) == 0
+    # host-side checks come first and never touch the pointers
+    assert L.vt_build_t2d(None, 10, V, FAKE, FAKE, wsb, None) == 1
+    assert L.vt_build_t2d(FAKE, 0, V, FAKE, FAKE, wsb, None) == 2
+    assert L.vt_build_t2d(FAKE, V + 1, V, FAKE, FAKE, wsb, None) == 2
+    assert L.vt_build_t2d(FAKE, 10, V, FAKE, None, 0, None) == 6
+    assert L.vt_build_t2d(FAKE + 2, 10, V, FAKE, FAKE, wsb, None) == 7
+    assert L.vt_coverage(None, 10, FAKE, V, None, FAKE, FAKE, wsb, None) == 1
+    assert L.vt_coverage(FAKE, 10, FAKE, V, None, None, FAKE, wsb, None) == 1
+    assert L.vt_coverage(FAKE, 0, FAKE, V, None, FAKE, FAKE, wsb, None) == 2
+    assert L.vt_coverage(FAKE, 10, FAKE, V, None, FAKE, FAKE, wsb - 1, None) == 6
+    assert L.vt_coverage(FAKE, 10, FAKE, V, FAKE + 1, FAKE, FAKE, wsb, None) == 7
