@@ -25,10 +25,13 @@ namespace vt {
 // tile 1: 256 tokens x 256 rows, 8 waves (2x4), 128x64 per wave (128 accumulators, two waves per
 //         SIMD hide each other's LDS / barrier / epilogue stalls; operand traffic from L2 is that
 //         of the largest tile): k <= 16, H % 64 == 0.
+// tile 2: 32 tokens x 128 rows, 4 waves (1x4), 32x32 per wave: for at most 128 rows over a narrow
+//         vocabulary, where 128-token tiles would leave most compute units without a workgroup
+//         (the shape is bound by reading W_sub once, not by the matrix cores).
 struct TileInfo {
     int BMV, BNR, parts_per_vtile;
 };
-static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}};
+static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}, {32, 128, 2}};
 
 void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 {
@@ -39,7 +42,9 @@ void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
 
 int gemm_pick_tile(int rows, int H, int Vd, int KP)
 {
-    (void)Vd;
+    // one row tile and fewer 128-token tiles than three quarters of the compute units: narrow tiles
+    if (rows <= 128 && (Vd + 127) / 128 < 192)
+        return 2;
     // the large tile has no K-tail variant and no room for long candidate lists
     if (KP > 16 || rows <= 128 || (H % 64) != 0)
         return 0;

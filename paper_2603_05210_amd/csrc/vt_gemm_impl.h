@@ -311,7 +311,6 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
     using C3 = std::integral_constant<int, 3>;
     constexpr int NMF = SV * SR;   // MFMAs per K-step
     constexpr int NFR = SV + SR;   // fragment reads per K-step
-    static_assert(NFR <= NMF && NLD <= 2 * NMF, "a K-step must have room for its memory operations");
 
     // One K-step: the MFMAs of fragment set SET, with the LDS reads of the next K-step's
     // fragments (from rd_next into the other set) issued one per MFMA.  In the two-stage pipeline
@@ -330,19 +329,29 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
         constexpr bool do_write = decltype(DO_WRITE)::value;
         constexpr bool do_load = decltype(DO_LOAD)::value;
         constexpr int SPACING = NMF / NPAIR > 0 ? NMF / NPAIR : 1;
+        constexpr int RPS = (NFR + NMF - 1) / NMF;    // fragment reads attached to one MFMA (1 unless the tile is small)
+        constexpr int PPS = (NPAIR + NMF - 1) / NMF;  // staging pieces attached to one MFMA (likewise)
         static_for<NMF>([&](auto M) {
             constexpr int m = decltype(M)::value;
             mfma_one(SET, M);
-            if constexpr (do_read && m < NFR)
-                read_one(rd_next, KSN, std::integral_constant<int, set ^ 1>{}, M);
-            if constexpr ((do_write || do_load) && (m % SPACING) == SPACING - 1 && (m / SPACING) < NPAIR) {
-                constexpr int i = ks * NPAIR + m / SPACING;
-                if constexpr (i < NLD) {
-                    if constexpr (do_write)
-                        store_one(wr, std::integral_constant<int, i>{});
-                    if constexpr (do_load)
-                        load_one(kt_load, std::integral_constant<int, i>{});
-                }
+            if constexpr (do_read) {
+                static_for<RPS>([&](auto Q) {
+                    constexpr int f = m + decltype(Q)::value * NMF;
+                    if constexpr (f < NFR)
+                        read_one(rd_next, KSN, std::integral_constant<int, set ^ 1>{}, std::integral_constant<int, f>{});
+                });
+            }
+            if constexpr ((do_write || do_load) && (m % SPACING) == SPACING - 1) {
+                static_for<PPS>([&](auto Q) {
+                    constexpr int pr = m / SPACING + decltype(Q)::value * NMF;
+                    constexpr int i = ks * NPAIR + pr;
+                    if constexpr (pr < NPAIR && i < NLD) {
+                        if constexpr (do_write)
+                            store_one(wr, std::integral_constant<int, i>{});
+                        if constexpr (do_load)
+                            load_one(kt_load, std::integral_constant<int, i>{});
+                    }
+                });
             }
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -421,6 +430,8 @@ static hipError_t launch_gemm_kp(const Plan& p, const GemmArgs& ga, hipStream_t 
 {
     if (p.tile == 0)
         return launch_tile<2, 2, 2, 2, KP, true>(p, ga, s);
+    if (p.tile == 2)
+        return launch_tile<1, 4, 1, 1, KP, true>(p, ga, s);
     if constexpr (KP <= 16) {
         if (p.tile == 1)
             return launch_tile<2, 4, 4, 2, KP, false>(p, ga, s);
