@@ -1,16 +1,18 @@
 // Streaming regime of the draft head (1..16 hidden-state rows): the projection of Section
 // 2.3 of the paper, z[r,j] = sum_i h[r,i] W_sub[j,i], is bound by reading W_sub once from
-// HBM (2*H*V_draft bytes, the same number as the paper's 2dk FLOP count), so the kernel is a
-// row-split dot product.
+// HBM (2*H*V_draft bytes, the same number as the paper's 2dk FLOP count), so the kernels
+// split W_sub by rows over the compute units and stream it exactly once.
 //
 // A workgroup of 16 waves owns a contiguous range of at most kGemvMaxRowsPerBlock W_sub rows.
-// A wave reads J consecutive rows at a time, one coalesced 128-bit load per lane per KiB,
-// multiplies them against the hidden states held in LDS (bf16 pairs through v_dot2_f32_bf16,
-// fp32 accumulation) and reduces across its 64 lanes on the VALU (DPP / permlane swaps).  The
-// logits of the range are parked in LDS, never in memory (except in the test hook).  When the
-// range is done, wave r reduces hidden-state row r: softmax statistics and the k best logits
-// of the range by k rounds of a wave-wide arg-max under the (logit, lower index) order.  One
-// partial per (row, workgroup) goes to the merge kernel.
+// Two forms of the stream: gemv_head_kernel (dot products: a wave reads J consecutive rows at a
+// time, one coalesced 128-bit load per lane per KiB, multiplies them against the hidden states
+// held in LDS through v_dot2_f32_bf16 with fp32 accumulation and reduces across its 64 lanes by
+// DPP / permlane swaps) and gemv_mfma_kernel (five rows or more: 16 W_sub rows at a time through
+// v_mfma_f32_16x16x32_bf16, described there).  The logits of the range are parked in LDS, never
+// in memory (except in the test hook).  When the range is done, wave r reduces hidden-state
+// row r: softmax statistics and the k best logits of the range by k rounds of a wave-wide
+// arg-max under the (logit, lower index) order.  One partial per (row, workgroup) goes to the
+// merge kernel, or, for one or two rows, to the last workgroup of the same launch.
 #include <atomic>
 #include <type_traits>
 
@@ -40,6 +42,8 @@ struct GemvArgs {
 
 // Arrival counters for the fused merge, one per in-flight call (the host hands out slots
 // round-robin); zero when idle: the last workgroup of a call puts its slot back to zero.
+// Calls on one stream run in order and may reuse a slot freely; across streams at most
+// kTicketSlots fused calls may be in flight at once.
 //
 // No cache-wide fences are used: the partial results are a few hundred bytes per workgroup and
 // travel through device-coherent accesses (relaxed agent-scope atomics: they bypass the
