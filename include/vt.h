@@ -88,7 +88,7 @@ vt_status vt_validate_draft_head_args(const void *h, int64_t rows, int64_t H, co
  * A pure function of its arguments: it does not depend on the device. */
 size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k);
 
-/* Which kernel family serves this shape: 0 = streaming row-split dot product (memory bound,
+/* Which kernel family serves this shape: 0 = streaming row-split kernels (memory bound,
  * rows <= 16), 1 = bf16 MFMA thin GEMM (rows > 16); -1 on invalid arguments. */
 int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
 
@@ -106,7 +106,10 @@ int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
  *                   contents need not be initialised and are clobbered
  *
  * Asynchronous on `stream`: no allocation, no synchronisation, no host read.  Concurrent
- * calls must not share a workspace.  The logits are never written to memory.
+ * calls must not share a workspace, and at most 1024 one- or two-row calls may be in flight at
+ * once across streams (their single-launch merge keeps one arrival counter per call in a
+ * table of that size; calls on one stream run in order and are not limited).  The logits are
+ * never written to memory.
  */
 vt_status vt_draft_head(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
                         const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
