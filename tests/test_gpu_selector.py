@@ -82,6 +82,14 @@ def test_paper_sized_selection(alpha, c_min):
     assert vt.vt_check_token_ids_host(ora.token_ids, V_PAPER) == vt.VT_OK
 
 
+def test_selection_at_the_benchmarked_size():
+    """The configuration bench.py times: 32 Mi tokens over LLaMA-3's vocabulary."""
+    _say("select at the benchmarked size")
+    tokens = synth.zipf_token_stream(0, V_PAPER, 32 * 1024 * 1024)
+    res, ora = _run_both(tokens, V_PAPER, D_PAPER, F_FIXED, 0.5, 0.9, 1024, V_PAPER)
+    _say("  k*=%d C=%.4f R=%.4f U=%.4f" % (res.k_star, res.C, res.R, res.U))
+
+
 def test_selected_ids_build_a_subset():
     V, H = 3000, 64
     tokens = synth.zipf_token_stream(2, V, 200_000)
