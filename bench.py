@@ -186,11 +186,12 @@ def cpu_baseline(runner, w, st):
 
 
 def kernel_source_hash():
-    """sha256 over the HIP sources: recorded with profiler counters so stale counters are not reported."""
+    """sha256 over the HIP sources of the draft-head kernels (everything but the selection and
+    coverage files): recorded with profiler counters so stale counters are not reported."""
     import hashlib
     h = hashlib.sha256()
     for f in sorted((ROOT / "paper_2603_05210_amd" / "csrc").glob("*")):
-        if f.suffix in (".hip", ".h"):
+        if f.suffix in (".hip", ".h") and not f.name.startswith(("vt_select", "vt_coverage")):
             h.update(f.name.encode())
             h.update(f.read_bytes())
     return h.hexdigest()
