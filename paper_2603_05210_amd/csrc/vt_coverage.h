@@ -8,7 +8,7 @@
 namespace vt {
 
 struct CoverageLayout {
-    size_t off_seen, off_counters, off_err, total;
+    size_t off_seen, off_inv, off_counters, off_err, total;
 };
 
 CoverageLayout coverage_layout(int64_t V);

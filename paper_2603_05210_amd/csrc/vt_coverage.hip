@@ -71,6 +71,69 @@ __global__ void __launch_bounds__(kCovThreads) coverage_kernel(const int32_t* __
         atomicAdd(&counters[0], covered);
 }
 
+// The same pass with both bitmaps in LDS, for vocabularies whose two V-bit maps fit there and
+// calls that do not want the mapped stream: the in-vocabulary map is built once per call in
+// memory and copied in, membership and "seen" are LDS bit operations, and the only per-token
+// memory traffic is the stream itself.  A workgroup merges its "seen" words into the global
+// bitmap when it is done.
+constexpr int kCovLdsThreads = 1024;
+
+__global__ void invocab_bitmap_kernel(const int32_t* __restrict__ t2d, int V, uint32_t* __restrict__ inv)
+{
+    const int w = blockIdx.x * blockDim.x + threadIdx.x;
+    const int words = (V + 31) >> 5;
+    if (w >= words)
+        return;
+    uint32_t bits = 0u;
+    for (int b = 0; b < 32; ++b) {
+        const int v = (w << 5) + b;
+        if (v < V && t2d[v] >= 0)
+            bits |= 1u << b;
+    }
+    inv[w] = bits;
+}
+
+__global__ void __launch_bounds__(kCovLdsThreads) coverage_lds_kernel(const int32_t* __restrict__ tokens, int64_t n,
+                                                                      const uint32_t* __restrict__ inv, int V,
+                                                                      uint32_t* __restrict__ seen,
+                                                                      unsigned long long* __restrict__ counters,
+                                                                      int* __restrict__ err)
+{
+    extern __shared__ uint32_t cov_lds[];
+    const int words = (V + 31) >> 5;
+    uint32_t* s_inv = cov_lds;
+    uint32_t* s_seen = cov_lds + words;
+    for (int w = threadIdx.x; w < words; w += kCovLdsThreads) {
+        s_inv[w] = inv[w];
+        s_seen[w] = 0u;
+    }
+    __syncthreads();
+    unsigned long long covered = 0;
+    auto take = [&](int t) {
+        if (t < 0 || t >= V) {
+            atomicOr(err, 1);
+            return;
+        }
+        const uint32_t bit = 1u << (t & 31);
+        covered += (s_inv[t >> 5] & bit) ? 1u : 0u;
+        if ((s_seen[t >> 5] & bit) == 0u)
+            atomicOr(&s_seen[t >> 5], bit);
+    };
+    const int64_t stride = (int64_t)gridDim.x * kCovLdsThreads;
+    for (int64_t i = (int64_t)blockIdx.x * kCovLdsThreads + threadIdx.x; i < n; i += stride)
+        take(__builtin_nontemporal_load(tokens + i));
+    for (int off = 32; off > 0; off >>= 1)
+        covered += __shfl_xor(covered, off, 64);
+    if ((threadIdx.x & 63) == 0 && covered != 0)
+        atomicAdd(&counters[0], covered);
+    __syncthreads();
+    for (int w = threadIdx.x; w < words; w += kCovLdsThreads) {
+        const uint32_t bits = s_seen[w];
+        if (bits != 0u)
+            atomicOr(&seen[w], bits);
+    }
+}
+
 // distinct tokens, and distinct tokens with a draft index, from the bitmap of seen tokens
 __global__ void __launch_bounds__(kCovThreads) unique_kernel(const uint32_t* __restrict__ seen,
                                                              const int32_t* __restrict__ t2d, int V,
@@ -104,7 +167,8 @@ CoverageLayout coverage_layout(int64_t V)
     CoverageLayout L;
     auto up = [](size_t x) { return (x + 255) / 256 * 256; };
     L.off_seen = 0;
-    L.off_counters = up((size_t)((V + 31) / 32) * sizeof(uint32_t));
+    L.off_inv = up((size_t)((V + 31) / 32) * sizeof(uint32_t));
+    L.off_counters = L.off_inv + up((size_t)((V + 31) / 32) * sizeof(uint32_t));
     L.off_err = L.off_counters + 256;
     L.total = L.off_err + 256;
     return L;
@@ -129,12 +193,29 @@ hipError_t launch_coverage(const int32_t* tokens, int64_t n, const int32_t* t2d,
     hipError_t e = hipMemsetAsync(ws, 0, L.total, s);
     if (e != hipSuccess)
         return e;
-    int64_t blocks = (n + kCovThreads * 16 - 1) / (kCovThreads * 16);
-    if (blocks > 2048)
-        blocks = 2048;
-    hipLaunchKernelGGL(coverage_kernel, dim3((unsigned)blocks), dim3(kCovThreads), 0, s, tokens, n, t2d, V, draft_ids,
-                       seen, counters, err);
     const int words = (V + 31) >> 5;
+    const size_t lds = (size_t)words * 2 * sizeof(uint32_t);
+    if (draft_ids == nullptr && lds <= 128 * 1024 && n >= (int64_t)1 << 20) {
+        // ratios only, long stream: bitmaps in LDS, one workgroup per compute unit
+        uint32_t* inv = reinterpret_cast<uint32_t*>(ws + L.off_inv);
+        hipLaunchKernelGGL(invocab_bitmap_kernel, dim3((words + 255) / 256), dim3(256), 0, s, t2d, V, inv);
+        static size_t lds_allowed = 48 * 1024;  // raised once, then remembered
+        if (lds > lds_allowed) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(coverage_lds_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess)
+                return e;
+            lds_allowed = lds;
+        }
+        hipLaunchKernelGGL(coverage_lds_kernel, dim3(256), dim3(kCovLdsThreads), lds, s, tokens, n, inv, V, seen,
+                           counters, err);
+    } else {
+        int64_t blocks = (n + kCovThreads * 16 - 1) / (kCovThreads * 16);
+        if (blocks > 2048)
+            blocks = 2048;
+        hipLaunchKernelGGL(coverage_kernel, dim3((unsigned)blocks), dim3(kCovThreads), 0, s, tokens, n, t2d, V,
+                           draft_ids, seen, counters, err);
+    }
     int ub = (words + kCovThreads - 1) / kCovThreads;
     if (ub > 256)
         ub = 256;

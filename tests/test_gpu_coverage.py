@@ -29,7 +29,9 @@ def _check(tokens, d2t, V):
     assert res.freq_coverage == ora.freq_coverage and res.unique_coverage == ora.unique_coverage
     assert np.array_equal(draft.cpu().numpy(), ora.draft_ids), "mapped stream differs"
     res2, none = vt.vt_coverage(_dev(tokens), t2d_dev)          # without the mapped stream
-    assert none is None and int(res2.n_covered) == ora.n_covered and int(res2.n_unique) == ora.n_unique
+    assert none is None
+    got2 = (int(res2.n_tokens), int(res2.n_covered), int(res2.n_unique), int(res2.n_unique_covered))
+    assert got2 == got and res2.freq_coverage == ora.freq_coverage and res2.unique_coverage == ora.unique_coverage
     return res, ora
 
 
@@ -39,6 +41,8 @@ def _check(tokens, d2t, V):
     (5000, 700, 300_001, 3000),
     (128256, 13264, 2_000_000, 128256),   # the paper's vocabulary and its selected size
     (128256, 128256, 500_000, 128256),    # the full vocabulary covers everything
+    (128256, 4380, 3_000_001, 90_000),    # long stream: the ratios-only call keeps its bitmaps in LDS
+    (300_000, 20_000, 1_500_000, 300_000),  # long stream, vocabulary a little too wide for that
     (1000, 1, 10_000, 1000),
 ])
 def test_coverage_matches_oracle(V, Vd, n, support):
