@@ -82,6 +82,10 @@ EDGE = [
     (9, 256, 131000, 130000, 5),
     (16, 512, 70000, 69000, 16),
     (16, 4096, 70000, 65536, 8),  # hidden states leave no LDS for staging: direct-load form
+    (1, 16384, 3000, 2500, 10),   # a very wide hidden state, one row
+    (16, 8192, 2000, 1500, 5),    # 16 rows whose hidden states do not fit LDS: matrix-core regime
+    (2048, 64, 600, 500, 4),      # many rows, narrow everything
+    (1, 2048, 130000, 128256, 64),  # longest list over the widest vocabulary
     (129, 64, 700, 257, 16),      # one row and one token past a tile edge
     (256, 128, 2000, 512, 16),    # exact tile multiples
 ]
