@@ -49,7 +49,8 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
     //   pass 2  sum of exp(z - max), and the (logit, token) pairs that make up those KP values:
     //           every element above the KP-th value, plus the earliest elements equal to it
     //           until KP are taken -- the lower-index-wins rule.
-    // The KP survivors are sorted best-first and stored as this stream's partial result.
+    // The KP survivors are stored as this stream's partial result (sorted best-first only when
+    // KP > 16).
     __syncthreads();  // every wave is done with the operand tiles
     constexpr int NE = SV * 16;   // elements per stream
     constexpr int NG = NE / 4;    // 4-element groups
@@ -153,7 +154,8 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
         // a stream shorter than KP leaves slots open: close them with the empty marker
         for (int sl = cnt; sl < KP; ++sl)
             ep_list[sl * 64 + lane] = make_int2(__float_as_int(neg_inf()), kIdxNone);
-        // the survivors, sorted best first
+        // the survivors; short lists leave the ordering to the merge kernel, which sorts only the
+        // few lists per row that can still contribute (their best logit is in the statistics)
         TopList<KP> L;
         static_for<KP>([&](auto S) {
             constexpr int sl = decltype(S)::value;
@@ -161,7 +163,8 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
             L.v[sl] = __int_as_float(e.x);
             L.i[sl] = e.y;
         });
-        L.sort();
+        if constexpr (KP > 16)
+            L.sort();
         if (row_ok) {
             const size_t slot = (size_t)row * a.P + part;
             if constexpr (KP >= 4) {

@@ -1,11 +1,11 @@
 // Final stage of a draft step and the one-time subset construction.
 //
 // merge_kernel: per hidden-state row, combines the P partial results (softmax statistics and
-// sorted candidate lists) that the projection kernel left in the workspace into the row's
-// log-sum-exp over V_d and its k best draft tokens, then maps them through the
-// draft-to-target buffer (Section 1 of the paper: EAGLE-3 style d2t) and emits
-// log-probabilities.  The merge uses the strict (logit, index) order, so its result does not
-// depend on how the vocabulary was split.
+// candidate lists of KP entries; lists longer than 16 arrive sorted, shorter ones in any order)
+// that the projection kernel left in the workspace into the row's log-sum-exp over V_d and its
+// k best draft tokens, then maps them through the draft-to-target buffer (Section 1 of the
+// paper: EAGLE-3 style d2t) and emits log-probabilities.  The merge uses the strict
+// (logit, index) order, so its result does not depend on how the vocabulary was split.
 //
 // check_ids / gather kernels: Section 2.1's V_d as a list of token ids -> W_sub and d2t.
 #include "vt_device.h"
@@ -86,7 +86,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         const size_t slot = (size_t)r * P + p;
         const float* pv = part_val + slot * KP;
         const int32_t* pi = part_idx + slot * KP;
-        if (first) {  // the first list a thread keeps is taken as it is (partial lists are sorted)
+        if (first) {  // the first list a thread keeps is taken whole
             if constexpr (KP % 4 == 0) {  // workspace and its sections are 16-byte aligned: 128-bit loads
 #pragma unroll
                 for (int q = 0; q < KP; q += 4) {
@@ -102,14 +102,20 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                     L.i[q] = pi[q];
                 }
             }
+            if constexpr (KP <= 16)
+                L.sort();  // short lists may arrive unsorted from the matrix-core kernels
             first = false;
-        } else {  // later lists: sorted, so stop at the first entry that cannot enter
+        } else {  // later lists (rare): entry by entry; long lists are sorted, so they may stop early
 #pragma unroll 1
             for (int q = 0; q < KP; ++q) {
                 const float x = pv[q];
                 const int ix = pi[q];
-                if (!better(x, ix, L.v[KP - 1], L.i[KP - 1]))
-                    break;
+                if (!better(x, ix, L.v[KP - 1], L.i[KP - 1])) {
+                    if constexpr (KP > 16)
+                        break;
+                    else
+                        continue;
+                }
                 L.insert(x, ix);
             }
         }
