@@ -134,23 +134,44 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
         int quota = KP;  // how many elements equal to thr belong to the KP best
         static_for<KP>([&](auto S) { quota -= (top[decltype(S)::value] > thr) ? 1 : 0; });
         const float mref = mx > neg_inf() ? mx : 0.0f;  // an all-masked stream sums exp(-inf) = 0
-        // pass 2
+        // pass 2, common case: every element >= thr is a survivor (at most KP of them unless the
+        // KP-th value is tied beyond its quota, which the count n_ge reveals afterwards)
+        constexpr float kLog2e = 1.4426950408889634f;
+        const float mref_l2 = mref * kLog2e;
         float ssum = 0.0f;
-        int cnt = 0;
+        int cnt = 0, n_ge = 0;
         for_each_group([&](const f32x4& v, int t0) {
             static_for<4>([&](auto C) {
                 constexpr int c = decltype(C)::value;
                 const float z = v[c];
-                ssum += __expf(z - mref);
-                const bool eq = (z == thr) && (quota > 0);
-                quota -= eq ? 1 : 0;
-                if (((z > thr) || eq) && cnt < KP) {
+                ssum += __builtin_amdgcn_exp2f(__builtin_fmaf(z, kLog2e, -mref_l2));
+                const bool take = z >= thr;
+                n_ge += take ? 1 : 0;
+                if (take && cnt < KP) {
                     const int tok = t0 + c;
                     ep_list[cnt * 64 + lane] = make_int2(__float_as_int(z), tok < a.Vd ? tok : kIdxNone);
                     ++cnt;
                 }
             });
         });
+        if (__builtin_amdgcn_ballot_w64(n_ge > KP) != 0ull) {
+            // some lane has more elements equal to thr than belong to its KP best: take the
+            // elements above thr and only the earliest `quota` equal ones (lower index wins)
+            cnt = 0;
+            for_each_group([&](const f32x4& v, int t0) {
+                static_for<4>([&](auto C) {
+                    constexpr int c = decltype(C)::value;
+                    const float z = v[c];
+                    const bool eq = (z == thr) && (quota > 0);
+                    quota -= eq ? 1 : 0;
+                    if (((z > thr) || eq) && cnt < KP) {
+                        const int tok = t0 + c;
+                        ep_list[cnt * 64 + lane] = make_int2(__float_as_int(z), tok < a.Vd ? tok : kIdxNone);
+                        ++cnt;
+                    }
+                });
+            });
+        }
         // a stream shorter than KP leaves slots open: close them with the empty marker
         for (int sl = cnt; sl < KP; ++sl)
             ep_list[sl * 64 + lane] = make_int2(__float_as_int(neg_inf()), kIdxNone);
