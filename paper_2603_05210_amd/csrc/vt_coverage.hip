@@ -9,6 +9,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "vt.h"
 #include "vt_coverage.h"
 
@@ -199,13 +201,13 @@ hipError_t launch_coverage(const int32_t* tokens, int64_t n, const int32_t* t2d,
         // ratios only, long stream: bitmaps in LDS, one workgroup per compute unit
         uint32_t* inv = reinterpret_cast<uint32_t*>(ws + L.off_inv);
         hipLaunchKernelGGL(invocab_bitmap_kernel, dim3((words + 255) / 256), dim3(256), 0, s, t2d, V, inv);
-        static size_t lds_allowed = 48 * 1024;  // raised once, then remembered
-        if (lds > lds_allowed) {
+        static std::atomic<size_t> lds_allowed{48 * 1024};  // raised once, then remembered
+        if (lds > lds_allowed.load()) {
             e = hipFuncSetAttribute(reinterpret_cast<const void*>(coverage_lds_kernel),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess)
                 return e;
-            lds_allowed = lds;
+            lds_allowed.store(lds);
         }
         hipLaunchKernelGGL(coverage_lds_kernel, dim3(256), dim3(kCovLdsThreads), lds, s, tokens, n, inv, V, seen,
                            counters, err);

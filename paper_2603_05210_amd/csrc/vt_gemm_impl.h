@@ -2,6 +2,7 @@
 // candidate-list length so that the instantiations compile in parallel.
 #pragma once
 
+#include <atomic>
 #include <type_traits>
 
 #include "vt_device.h"
@@ -437,13 +438,13 @@ static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
         if (guard)
             return hipErrorInvalidValue;
     }
-    static bool lds_raised[2] = {false, false};  // per instantiation and variant: raised once
-    if (lds > 48 * 1024 && !lds_raised[guard]) {
+    static std::atomic<bool> lds_raised[2] = {{false}, {false}};  // per instantiation and variant: raised once
+    if (lds > 48 * 1024 && !lds_raised[guard].load()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess)
             return e;
-        lds_raised[guard] = true;
+        lds_raised[guard].store(true);
     }
     hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(NT), lds, s, ga);
     return hipGetLastError();

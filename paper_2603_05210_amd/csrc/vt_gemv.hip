@@ -528,13 +528,13 @@ static hipError_t launch_mfma(const Plan& p, const GemvArgs& ga, hipStream_t s)
     if (lds > (size_t)kGemvLdsLimit)
         return hipErrorInvalidValue;
     auto kern = staged ? gemv_mfma_kernel<true> : gemv_mfma_kernel<false>;
-    static size_t lds_allowed[2] = {48 * 1024, 48 * 1024};  // per variant: raised once, then remembered
-    if (lds > lds_allowed[staged]) {
+    static std::atomic<size_t> lds_allowed[2] = {{48 * 1024}, {48 * 1024}};  // per variant: raised once, then remembered
+    if (lds > lds_allowed[staged].load()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess)
             return e;
-        lds_allowed[staged] = lds;
+        lds_allowed[staged].store(lds);
     }
     hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
     return hipGetLastError();
@@ -553,13 +553,13 @@ static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
     auto kern = gemv_head_kernel<NR, J, DOT2>;
     if (lds > (size_t)kGemvLdsLimit)
         return hipErrorInvalidValue;
-    static size_t lds_allowed = 48 * 1024;  // per instantiation: raised once, then remembered
-    if (lds > lds_allowed) {
+    static std::atomic<size_t> lds_allowed{48 * 1024};  // per instantiation: raised once, then remembered
+    if (lds > lds_allowed.load()) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess)
             return e;
-        lds_allowed = lds;
+        lds_allowed.store(lds);
     }
     hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
     return hipGetLastError();

@@ -15,6 +15,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "vt.h"
 #include "vt_select.h"
 
@@ -392,13 +394,13 @@ hipError_t launch_select(const int32_t* tokens, int64_t n, int V, const SelectPa
         return e;
     // one workgroup per compute unit (128 KiB of LDS each), fewer for short streams
     constexpr size_t hist_lds = (size_t)kHistSlots * 8;
-    static bool lds_raised = false;
-    if (!lds_raised) {
+    static std::atomic<bool> lds_raised{false};
+    if (!lds_raised.load()) {
         e = hipFuncSetAttribute(reinterpret_cast<const void*>(hist_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)hist_lds);
         if (e != hipSuccess)
             return e;
-        lds_raised = true;
+        lds_raised.store(true);
     }
     int64_t hb = (n + (int64_t)kHistThreads * 64 - 1) / ((int64_t)kHistThreads * 64);
     if (hb > 256)
