@@ -53,8 +53,16 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         // fusing pays while one workgroup can finish all rows in one pass
         p.fused = (rows <= 2 && p.P <= 256 && p.KP <= 16) ? 1 : 0;
         // five rows or more: matrix-core variant (measured: 93.6 vs 104 us at 8 rows, 96 vs 165 us at
-        // 16; the dot-product form wins up to 4 rows), while every wave gets a 16-row group
-        p.mfma = (rows >= 5 && H % 256 == 0 && p.rpb >= 16 * kGemvWaves) ? 1 : 0;
+        // 16; the dot-product form wins up to 4 rows).  A range with fewer 16-row groups than the
+        // workgroup has waves is also cut along the hidden dimension (ks slices per group).
+        p.mfma = (rows >= 5 && H % 256 == 0) ? 1 : 0;
+        p.ks = 1;
+        if (p.mfma) {
+            const int groups = (p.rpb + 15) / 16;
+            const int iters = (int)(H / 256);
+            while (groups * p.ks < kGemvWaves && iters % (p.ks * 2) == 0)
+                p.ks *= 2;
+        }
     } else {
         p.regime = 1;
         p.tile = gemm_pick_tile((int)rows, (int)H, (int)Vd, p.KP);

@@ -28,6 +28,7 @@ struct GemvArgs {
     const u32x4* h;
     const u32x4* W;
     int rows, nchunk, Vd, P, k, KP, rpb;  // rpb: W_sub rows per workgroup (multiple of J)
+    int ks;  // slices of the hidden dimension whose partial logits sit side by side in LDS (1: none)
     float* part_val;
     int32_t* part_idx;
     float2* part_stat;
@@ -143,6 +144,7 @@ __device__ __forceinline__ float dot8(const u32x4& w, const u32x4& x, float acc)
 // [j_lo, j_lo + n_local) are in LDS (zbuf[row][rpb]): per hidden-state row the softmax
 // partial and the k best of the range, written as one partial result; then, when the call is
 // fused, the last workgroup to arrive merges all partial results and emits the outputs.
+template <bool STORE_LOGITS>
 __device__ __forceinline__ void block_tail(const GemvArgs& a, u32x4* smem, const float* zbuf, int tid, int j_lo,
                                            int n_local)
 {
@@ -163,7 +165,16 @@ __device__ __forceinline__ void block_tail(const GemvArgs& a, u32x4* smem, const
 #pragma unroll
             for (int i = 0; i < VPL; ++i) {
                 const int e = lane * VPL + i;
-                v[i] = (e < n_local) ? zbuf[r * a.rpb + e] : neg_inf();
+                v[i] = neg_inf();
+                if (e < n_local) {
+                    // zbuf[slice][row][rpb]: a logit is the sum of its slices' partial sums, in slice order
+                    float z = zbuf[r * a.rpb + e];
+                    for (int q = 1; q < a.ks; ++q)
+                        z += zbuf[(q * a.rows + r) * a.rpb + e];
+                    v[i] = z;
+                    if (STORE_LOGITS && a.logits_out != nullptr)
+                        a.logits_out[(size_t)r * a.Vd + j_lo + e] = z;
+                }
                 mloc = fmaxf(mloc, v[i]);
             }
             m = wave_max(mloc);
@@ -358,7 +369,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
     }
     __syncthreads();
 
-    block_tail(a, smem, zbuf, tid, j_lo, n_local);
+    block_tail<false>(a, smem, zbuf, tid, j_lo, n_local);
 }
 
 // Matrix-core variant for several hidden-state rows (2..16): the same row-split stream of
@@ -368,7 +379,10 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_head_kernel(GemvArgs a)
 // step fall into distinct bank groups) as the B operand.  One MFMA, one 16-byte global load and
 // a few LDS accesses per lane per KiB of W_sub whatever the row count, and no cross-lane
 // reduction: lane l ends with the logits of hidden row l%16 for W_sub rows 4*(l/16)..+3 of
-// the group.  Needs H % 256 == 0 (8 KiB per wave and loop iteration).
+// the group.  Needs H % 256 == 0 (8 KiB per wave and loop iteration).  A narrow range (fewer
+// 16-row groups than waves) is also cut along the hidden dimension: work items are (group,
+// slice), every slice leaves partial logits in its own LDS plane, and the planes are added in
+// slice order when the range is reduced, so the result does not depend on timing.
 //
 // STAGED: global loads stay line-sized (a load instruction takes 128 contiguous bytes of each
 // of 8 rows; loading straight into the A layout touches 64 different lines per instruction and
@@ -388,14 +402,18 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int nchunk = a.nchunk;
-    float* zbuf = reinterpret_cast<float*>(smem + a.rows * nchunk);  // [rows][rpb]
-    u32x4* stage = reinterpret_cast<u32x4*>(zbuf + a.rows * a.rpb) + wave * kMfmaStage;  // STAGED only
+    float* zbuf = reinterpret_cast<float*>(smem + a.rows * nchunk);  // [ks][rows][rpb]
+    u32x4* stage = reinterpret_cast<u32x4*>(zbuf + a.ks * a.rows * a.rpb) + wave * kMfmaStage;  // STAGED only
 
     const int j_lo = blockIdx.x * a.rpb;
     const int j_hi = (j_lo + a.rpb < a.Vd) ? j_lo + a.rpb : a.Vd;
     const int n_local = j_hi - j_lo;
     const int ngroups = (n_local + kMfmaGroup - 1) / kMfmaGroup;
-    const int iters = nchunk / (4 * kMfmaUnroll);  // loop iterations per group (32 pieces each)
+    const int iters = nchunk / (4 * kMfmaUnroll) / a.ks;  // loop iterations per item (32 pieces each)
+    // work item = (group of 16 W_sub rows, slice of the hidden dimension): a narrow range has
+    // fewer groups than the workgroup has waves, so each group is cut into ks slices whose
+    // partial logits are added up when the range is reduced
+    const int nitems = ngroups * a.ks;
 
     const int lrow = lane & 15;
     const int kg = lane >> 4;
@@ -410,9 +428,11 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
     const int ld_piece_b = (lane & 7) ^ (((ld_row + 8) >> 1) & 7);  // rows 8..15
     const int a_sw = (lrow >> 1) & 7;
 
-    // position = (group g, iteration it); the loads of the next position are in flight while
-    // the current one is multiplied, also across groups
-    auto load_pos = [&](int gg, int it, u32x4(&buf)[kMfmaUnroll]) {
+    // position = (item, iteration it); the loads of the next position are in flight while the
+    // current one is multiplied, also across items
+    auto load_pos = [&](int item, int it_in, u32x4(&buf)[kMfmaUnroll]) {
+        const int gg = item / a.ks;
+        const int it = (item - gg * a.ks) * iters + it_in;
         if constexpr (STAGED) {
             const int jr = j_lo + gg * kMfmaGroup + ld_row;
             const int ja = jr < j_hi ? jr : j_hi - 1;  // a short last group re-reads the range's last row
@@ -441,11 +461,13 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
             itn = 0;
             gn = g + kGemvWaves;
         }
-        if (gn < ngroups)
+        if (gn < nitems)
             load_pos(gn, itn, nxt);
+        const int grp = g / a.ks;
+        const int slice = g - grp * a.ks;
 #pragma unroll
         for (int q = 0; q < kMfmaUnroll / 2; ++q) {
-            const int c0 = it * (4 * kMfmaUnroll) + 8 * q + kg;  // piece of the first 32-wide step
+            const int c0 = (slice * iters + it) * (4 * kMfmaUnroll) + 8 * q + kg;  // piece of the first 32-wide step
             u32x4 w0, w1;
             if constexpr (STAGED) {
                 stage[lane] = cur[2 * q];
@@ -472,12 +494,9 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
             if (lrow < a.rows) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const int e = g * kMfmaGroup + 4 * kg + i;
-                    if (e < n_local) {
-                        zbuf[lrow * a.rpb + e] = z[i];
-                        if (a.logits_out != nullptr)
-                            a.logits_out[(size_t)lrow * a.Vd + j_lo + e] = z[i];
-                    }
+                    const int e = grp * kMfmaGroup + 4 * kg + i;
+                    if (e < n_local)
+                        zbuf[(slice * a.rows + lrow) * a.rpb + e] = z[i];
                 }
             }
         }
@@ -485,7 +504,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
         g = gn;
     };
     u32x4 bufA[kMfmaUnroll], bufB[kMfmaUnroll];
-    if (g < ngroups)
+    if (g < nitems)
         load_pos(g, 0, bufA);  // in flight while the hidden states are staged
 
     for (int x = tid; x < a.rows * nchunk; x += kGemvThreads) {
@@ -494,20 +513,20 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_mfma_kernel(GemvArgs a)
         smem[r * nchunk + (c ^ (r & 15))] = a.h[x];
     }
     __syncthreads();
-    while (g < ngroups) {
+    while (g < nitems) {
         step(bufA, bufB);
-        if (g >= ngroups)
+        if (g >= nitems)
             break;
         step(bufB, bufA);
     }
     __syncthreads();
-    block_tail(a, smem, zbuf, tid, j_lo, n_local);
+    block_tail<true>(a, smem, zbuf, tid, j_lo, n_local);
 }
 
 // LDS bytes of the matrix-core streaming kernel without / with the staging buffers
-static size_t mfma_lds_bytes(int rows, int nchunk, int rpb, bool staged)
+static size_t mfma_lds_bytes(int rows, int nchunk, int rpb, int ks, bool staged)
 {
-    size_t lds = (size_t)rows * nchunk * sizeof(u32x4) + (size_t)rows * rpb * sizeof(float);
+    size_t lds = (size_t)rows * nchunk * sizeof(u32x4) + (size_t)ks * rows * rpb * sizeof(float);
     if (staged)
         lds += (size_t)kGemvWaves * kMfmaStage * sizeof(u32x4);
     return lds;
@@ -517,8 +536,10 @@ static hipError_t launch_mfma(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
     if (ga.nchunk % (4 * kMfmaUnroll) != 0 || ga.rows > 16)
         return hipErrorInvalidValue;
-    const bool staged = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, true) <= (size_t)kGemvLdsLimit;
-    size_t lds = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, staged);
+    if (ga.ks < 1 || (ga.nchunk / (4 * kMfmaUnroll)) % ga.ks != 0)
+        return hipErrorInvalidValue;
+    const bool staged = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, ga.ks, true) <= (size_t)kGemvLdsLimit;
+    size_t lds = mfma_lds_bytes(ga.rows, ga.nchunk, ga.rpb, ga.ks, staged);
     if (ga.fused) {
         if (ga.rows > kFusedMaxRows || ga.P > 256 || ga.KP > 16)
             return hipErrorInvalidValue;
@@ -577,6 +598,7 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.k = p.k;
     ga.KP = p.KP;
     ga.rpb = p.rpb;
+    ga.ks = p.mfma ? p.ks : 1;
     ga.part_val = a.part_val;
     ga.part_idx = a.part_idx;
     ga.part_stat = a.part_stat;

@@ -28,6 +28,7 @@ struct Plan {
     int rpb;     // W_sub rows per workgroup
     int fused;   // the streaming kernel's last workgroup also does the final merge
     int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
+    int ks;      // its slices of the hidden dimension per 16-row group (narrow ranges: keeps 16 waves busy)
     // GEMM regime
     int tile;    // index into the table of tile shapes
     int n_vtiles, n_rtiles;
