@@ -17,7 +17,7 @@ template <int KP>
 __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __restrict__ part_val,
                                                               const int32_t* __restrict__ part_idx,
                                                               const float2* __restrict__ part_stat, int P, int k,
-                                                              const int32_t* __restrict__ d2t,
+                                                              int lists_sorted, const int32_t* __restrict__ d2t,
                                                               int32_t* __restrict__ out_ids,
                                                               float* __restrict__ out_logp,
                                                               float* __restrict__ lse_out)
@@ -26,6 +26,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
     __shared__ float sm_val[KP > 16 ? NW : 1][KP];  // per-wave results (long lists only)
     __shared__ int sm_idx[KP > 16 ? NW : 1][KP];
     __shared__ float2 sm_stat[NW];
+    __shared__ int sm_qn;  // lists queued for the merge (short lists only)
 
     const int r = blockIdx.x;
     const int tid = threadIdx.x;
@@ -102,8 +103,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                     L.i[q] = pi[q];
                 }
             }
-            if constexpr (KP <= 16)
-                L.sort();  // short lists may arrive unsorted from the matrix-core kernels
+            if (KP <= 16 && !lists_sorted)
+                L.sort();  // short lists arrive unsorted from the matrix-core GEMM kernels
             first = false;
         } else {  // later lists (rare): entry by entry; long lists are sorted, so they may stop early
 #pragma unroll 1
@@ -127,7 +128,6 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         // the queue is merged on the spot by its owner.
         constexpr int QCAP = 2048;
         __shared__ int sm_queue[QCAP];
-        __shared__ int sm_qn;
         if (tid == 0)
             sm_qn = 0;
         __syncthreads();
@@ -189,7 +189,11 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         __syncthreads();
         if (wave != 0)
             return;
-        wave_walk_merge<KP, NW, false>(sl_val, sl_idx, kMergeThreads, k, lane, ov, oi);
+        // at most 64 queued lists sit in the first 64 threads: one head per lane then
+        if (sm_qn <= kWave)
+            wave_walk_merge<KP, 1, false>(sl_val, sl_idx, kWave, k, lane, ov, oi);
+        else
+            wave_walk_merge<KP, NW, false>(sl_val, sl_idx, kMergeThreads, k, lane, ov, oi);
     } else {
         wave_merge<KP>(L, true, lane, ov, oi, k);
         if (lane < KP) {
@@ -231,10 +235,12 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
 
 hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s)
 {
+    // the streaming kernels and long lists arrive sorted; the GEMM epilogue leaves short lists as they come
+    const int sorted = (p.regime == 0 || p.KP > 16) ? 1 : 0;
 #define VT_MERGE_CASE(KPV)                                                                                   \
     case KPV:                                                                                                \
         hipLaunchKernelGGL(merge_kernel<KPV>, dim3(p.rows), dim3(kMergeThreads), 0, s, a.part_val, a.part_idx, \
-                           a.part_stat, p.P, p.k, a.d2t, a.out_ids, a.out_logp, a.lse_out);                  \
+                           a.part_stat, p.P, p.k, sorted, a.d2t, a.out_ids, a.out_logp, a.lse_out);          \
         break;
     switch (p.KP) {
         VT_MERGE_CASE(1)
