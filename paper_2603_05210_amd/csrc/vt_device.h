@@ -39,22 +39,6 @@ struct TopList {
         }
     }
 
-    // Insert when candidates arrive in ascending index order: a newcomer displaces an entry
-    // only when strictly larger, which is exactly the lower-index-wins rule.
-    __device__ __forceinline__ void insert_ordered(float x, int ix)
-    {
-#pragma unroll
-        for (int s = 0; s < KP; ++s) {
-            const bool c = x > v[s];
-            const float tv = c ? v[s] : x;
-            const int ti = c ? i[s] : ix;
-            v[s] = c ? x : v[s];
-            i[s] = c ? ix : i[s];
-            x = tv;
-            ix = ti;
-        }
-    }
-
     // Insert with the full comparator (arrival order arbitrary).
     __device__ __forceinline__ void insert(float x, int ix)
     {
@@ -265,15 +249,6 @@ __device__ __forceinline__ void wave_best_ordered(int kv, int i, int& best_key, 
 }
 
 // Softmax partial (m, s) with s = sum exp(z - m) over some set; the empty set is (-inf, 0).
-__device__ __forceinline__ void stat_add(float& m, float& s, float z)
-{
-    const float mn = fmaxf(m, z);
-    if (mn > neg_inf()) {
-        s = s * __expf(m - mn) + __expf(z - mn);
-        m = mn;
-    }
-}
-
 __device__ __forceinline__ void stat_merge(float& m, float& s, float m2, float s2)
 {
     const float mn = fmaxf(m, m2);
@@ -395,56 +370,8 @@ __device__ __forceinline__ void wave_walk_merge(const float* lv, const int* li, 
     outv = key2f(outk);
 }
 
-// ---- the same reductions inside one DPP row (16 consecutive lanes), DPP only ----
+// ---- the same reduction inside one DPP row (16 consecutive lanes), DPP only ----
 __device__ __forceinline__ float row16_max(float x) { return key2f(row16_max_i(f2key(x))); }
-
-__device__ __forceinline__ float row16_sum(float x, int lane)
-{
-    x += xchg_f<1>(x, lane);
-    x += xchg_f<2>(x, lane);
-    x += xchg_f<4>(x, lane);
-    x += xchg_f<8>(x, lane);
-    return x;
-}
-
-__device__ __forceinline__ void row16_best(float& v, int& i)
-{
-    const int kv = f2key(v);
-    const int bk = row16_max_i(kv);
-    const int cand = (kv == bk) ? i : kIdxNone;
-    i = row16_min_i(cand);
-    v = key2f(bk);
-}
-
-// Combine the softmax partials of the 16 lanes of a row (inactive lanes pass (-inf, 0)).
-__device__ __forceinline__ void row16_stat_merge(float& m, float& s, int lane)
-{
-    const float M = row16_max(m);
-    const float t = (m > neg_inf()) ? s * __expf(m - M) : 0.0f;
-    s = row16_sum(t, lane);
-    m = M;
-}
-
-// Merge the sorted lists held by the 16 lanes of a row: after `rounds` (<= 16, <= KP) rounds
-// the lane with (lane % 16) == q holds the q-th best candidate of the union.  Lists are consumed.
-template <int KP>
-__device__ __forceinline__ void row16_merge(TopList<KP>& L, int rounds, int lane, float& outv, int& outi)
-{
-    outv = neg_inf();
-    outi = kIdxNone;
-#pragma unroll 1
-    for (int q = 0; q < rounds; ++q) {
-        float bv = L.v[0];
-        int bi = L.i[0];
-        row16_best(bv, bi);
-        if (L.i[0] == bi && L.v[0] == bv)
-            L.pop();
-        if ((lane & 15) == q) {
-            outv = bv;
-            outi = bi;
-        }
-    }
-}
 
 // Sum NP per-lane values across the wave so that lane l ends with the total of value number
 // p(l) = l >> (6 - log2 NP): each exchange halves the number of live values instead of
