@@ -251,6 +251,40 @@ def test_hip_graph_replays_match_eager(rows, H, Vd, k):
         assert junk == junk
 
 
+def test_calls_on_two_streams_do_not_disturb_each_other():
+    """Single-launch (one- and two-row) steps interleaved on two streams, each with its own
+    workspace and outputs: every call must give what it gives alone (the arrival counters of
+    concurrent calls are distinct)."""
+    H, Vd, k = 512, 20000, 10
+    W_dev = to_dev_bf16(synth.gen_W(77, Vd, H, std=0.05))
+    d2t_dev = torch.arange(Vd, dtype=torch.int32, device=DEV)
+    hs = {r: to_dev_bf16(synth.gen_h(50 + r, r, H)) for r in (1, 2)}
+    alone = {}
+    for r, h in hs.items():
+        a, b = vt.vt_draft_head(h, W_dev, d2t_dev, k)
+        torch.cuda.synchronize()
+        alone[r] = (a.cpu().numpy(), b.cpu().numpy())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]   # default priority
+    slots = []
+    for si, st in enumerate(streams):
+        for n in range(40):
+            r = 1 + (n + si) % 2
+            ws = torch.empty(vt.vt_draft_head_workspace_bytes(r, H, Vd, k), dtype=torch.uint8, device=DEV)
+            ids = torch.empty((r, k), dtype=torch.int32, device=DEV)
+            lp = torch.empty((r, k), dtype=torch.float32, device=DEV)
+            slots.append((si, r, ws, ids, lp))
+    torch.cuda.synchronize()
+    for n in range(40):
+        for si, st in enumerate(streams):
+            _, r, ws, ids, lp = slots[si * 40 + n]
+            with torch.cuda.stream(st):
+                vt.vt_draft_head(hs[r], W_dev, d2t_dev, k, ids, lp, ws)
+    torch.cuda.synchronize()
+    for si, r, ws, ids, lp in slots:
+        assert np.array_equal(ids.cpu().numpy(), alone[r][0])
+        assert np.array_equal(lp.cpu().numpy().view(np.uint32), alone[r][1].view(np.uint32))
+
+
 # ------------------------------------------------------------------ full-size workloads
 @pytest.fixture(scope="module")
 def W2048():
