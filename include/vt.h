@@ -204,7 +204,8 @@ vt_status vt_build_t2d(const int32_t *d2t, int64_t V_draft, int64_t V, int32_t *
 /*
  * Coverage of a draft vocabulary on a stream of token ids (Section 2.2, Eq. 2 evaluated on the
  * stream; Section 5.1, Table 4): the share of token occurrences whose token has a draft index
- * ("Freq. Cov.") and the share of distinct tokens of the stream that have one ("Unique Cov.").
+ * (the table's frequency-weighted column) and the share of distinct tokens of the stream that
+ * have one (its unique-token column).
  * Counts of several streams add up (Table 4's combined row).  Optionally writes the stream
  * mapped through t2d (-1 where the target token has no draft index), the remapping that masks
  * out-of-vocabulary targets.

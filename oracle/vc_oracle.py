@@ -32,8 +32,8 @@ class Coverage:
     n_covered: int           # occurrences whose token is in the draft vocabulary
     n_unique: int            # distinct tokens in the stream
     n_unique_covered: int    # distinct tokens in the stream that are in the draft vocabulary
-    freq_coverage: float     # n_covered / n_tokens          (Table 4 "Freq. Cov."; Eq. 2 on this stream)
-    unique_coverage: float   # n_unique_covered / n_unique   (Table 4 "Unique Cov.")
+    freq_coverage: float     # n_covered / n_tokens          (Table 4, frequency-weighted column; Eq. 2 on this stream)
+    unique_coverage: float   # n_unique_covered / n_unique   (Table 4, unique-token column)
     draft_ids: np.ndarray    # int32[n]: t2d[token], -1 where the target token has no draft index
 
 
@@ -54,7 +54,7 @@ def coverage(tokens: np.ndarray, t2d: np.ndarray) -> Coverage:
 
 
 def combine(parts) -> tuple[int, int, float]:
-    """Coverage of several streams taken together: occurrences add up (Table 4 "Combined")."""
+    """Coverage of several streams taken together: occurrences add up (the combined row of Table 4)."""
     n = sum(p.n_tokens for p in parts)
     c = sum(p.n_covered for p in parts)
     return n, c, c / n

@@ -39,7 +39,7 @@ def test_latency_reduction_matches_the_papers_printed_values(golden_dir):
     assert abs(2.0 * d * V / 1e6 - t["lm_head"][0]) < 0.05
     R = vs.latency_reduction(np.array([13264, 1, V]), d, V, F_fixed)
     assert abs(100.0 * R[0] - t["R_at_13264"][0]) < 0.05     # 57.5 % at the selected size
-    assert round(100.0 * R[1]) == t["R_max"][0]               # "up to 64 %"
+    assert round(100.0 * R[1]) == t["R_max"][0]               # the largest reduction the paper quotes
     assert R[2] == 0.0                                         # the full vocabulary saves nothing
     # the head's share of the draft's FLOPs is the limit of R as k -> 0 (64.15 from the table's
     # own rounded entries, printed as 64.2)
