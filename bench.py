@@ -276,7 +276,7 @@ def main():
         calibrate_copy()
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on exactly one GPU (the head shards by vocabulary or by rows "
+        print("bench.py: the head runs on exactly one GPU here (the head shards by vocabulary or by rows "
               "without changing the per-GPU kernel); use --gpus 1", file=sys.stderr)
         sys.exit(2)
     import torch

@@ -209,7 +209,7 @@ def small_int_bf16(seed: int, stream: int, shape, lo: int = -4, hi: int = 4) -> 
     return f32_to_bf16(v.astype(np.float32)).reshape(shape)
 
 
-# The five workload shapes this build is measured and tested on.
+# The five workload shapes the head is measured and tested on.
 CONFIGS = {
     "cfg0": dict(H=2048, rows=(1,), V_draft=(4096,), k=1, peaked=0.0),
     "cfg1": dict(H=2048, rows=(1, 4, 8), V_draft=(FULL_VOCAB,), k=10, peaked=0.0),

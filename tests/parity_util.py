@@ -1,6 +1,6 @@
 """Comparison of the HIP path's outputs with the CPU oracle's, element by element.
 
-Bar (stated for this build): the W_sub gather, d2t ids and top-k ids bit-exact -- except that a
+Bar: the W_sub gather, d2t ids and top-k ids bit-exact -- except that a
 top-k position whose two candidate tokens have oracle logits within TIE_TOL of each other is
 exempt -- and logits / log-probs within ABS_TOL absolute.  The only arithmetic difference
 between the two sides is the order of the fp32 additions (sequential on the CPU; per lane,
