@@ -18,7 +18,7 @@ struct SelectParams {
 
 struct SelectLayout {
     int N2;  // V rounded up to a power of two (at least one sort chunk)
-    size_t off_keys, off_mark, off_result, off_err, total;
+    size_t off_keys, off_mark, off_result, off_seg, off_err, total;
 };
 
 SelectLayout select_layout(int64_t V);

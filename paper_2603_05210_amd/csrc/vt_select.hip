@@ -176,11 +176,12 @@ __device__ __forceinline__ bool beats(const Best& a, const Best& b)  // larger u
     return a.u > b.u || (a.u == b.u && a.k < b.k);
 }
 
-// One workgroup of 16 waves.  Wave w owns a contiguous segment of ranks and walks it in tiles of
-// 64 (lane = rank within the tile: coalesced 512-byte loads).  Pass 1 sums the segment's
-// frequencies and writes the ranking; the 16 sums give every wave its starting prefix; pass 2
-// scans each tile across the lanes, evaluates Eq. 2-5 at every k of the range and keeps the best.
+// The passes over the V sorted keys are spread over up to kSegBlocks workgroups: workgroup b owns
+// the contiguous segment [b*seg, (b+1)*seg) of ranks (seg a multiple of 1024), walked in tiles
+// of 1024 (thread = rank within the tile: coalesced loads).  Cross-workgroup prefixes come from
+// a small array of per-segment sums written by a first kernel.
 constexpr int kScanWaves = kScanThreads / 64;
+constexpr int kSegBlocks = 256;
 
 __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long long x, int lane)
 {
@@ -193,50 +194,74 @@ __device__ __forceinline__ unsigned long long wave_incl_scan_u64(unsigned long l
     return x;
 }
 
-__global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* __restrict__ keys, int V, SelectParams prm,
-                                                               int32_t* __restrict__ rank_ids, vt_selection* __restrict__ out)
+// Sum of one value per thread over the workgroup; every thread returns it.  `scratch` has
+// kScanWaves entries and may be reused after the call.
+__device__ __forceinline__ unsigned long long block_sum_u64(unsigned long long x, unsigned long long* scratch)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const unsigned long long w = __shfl(wave_incl_scan_u64(x, lane), 63, 64);
+    __syncthreads();
+    if (lane == 0)
+        scratch[wave] = w;
+    __syncthreads();
+    unsigned long long tot = 0;
+    for (int i = 0; i < kScanWaves; ++i)
+        tot += scratch[i];
+    return tot;
+}
+
+struct BlockBest {
+    double u;       // penalised utility
+    long long k;
+    double C, R, U;
+    int feasible;
+};
+
+// pass 1: the ranking, and the sum of the frequencies of every segment
+__global__ void __launch_bounds__(kScanThreads) rank_sums_kernel(const uint64_t* __restrict__ keys, int V, int seg,
+                                                                 int32_t* __restrict__ rank_ids,
+                                                                 unsigned long long* __restrict__ seg_sum)
+{
+    __shared__ unsigned long long scratch[kScanWaves];
+    const int r0 = blockIdx.x * seg;
+    const int r1 = r0 + seg < V ? r0 + seg : V;
+    unsigned long long sum = 0;
+    for (int r = r0 + threadIdx.x; r < r1; r += kScanThreads) {
+        const uint64_t key = keys[r];
+        sum += key >> 32;
+        rank_ids[r] = (int32_t)(0xFFFFFFFFu - (uint32_t)key);
+    }
+    sum = block_sum_u64(sum, scratch);
+    if (threadIdx.x == 0)
+        seg_sum[blockIdx.x] = sum;
+}
+
+// pass 2: prefix sums, Eq. 2-5 at every k of the range, and the segment's best k
+__global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* __restrict__ keys, int V, int seg,
+                                                               SelectParams prm,
+                                                               const unsigned long long* __restrict__ seg_sum,
+                                                               BlockBest* __restrict__ seg_best)
 {
 #pragma clang fp contract(off)
-    __shared__ unsigned long long wsum[kScanWaves];
+    __shared__ unsigned long long scratch[kScanWaves];
     __shared__ Best best_s[kScanThreads];
     __shared__ int feas_s;
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = t >> 6;
-    const int seg = ((V + kScanWaves - 1) / kScanWaves + 63) & ~63;  // ranks per wave, whole tiles
-    const int r0 = wave * seg < V ? wave * seg : V;
-    const int r1 = r0 + seg < V ? r0 + seg : V;
+    const int nseg = gridDim.x;
     if (t == 0)
         feas_s = 0;
-
-    constexpr int TB = 8;  // tiles fetched together: the loop is bound by load latency otherwise
-    unsigned long long lsum = 0;
-    for (int rb = r0; rb < r1; rb += 64 * TB) {
-        uint64_t kb[TB];
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int r = rb + 64 * u + lane;
-            kb[u] = r < r1 ? keys[r] : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int r = rb + 64 * u + lane;
-            if (r < r1) {
-                lsum += kb[u] >> 32;
-                rank_ids[r] = (int32_t)(0xFFFFFFFFu - (uint32_t)kb[u]);
-            }
-        }
+    // frequencies before this segment, and in all segments
+    unsigned long long before = 0, all = 0;
+    for (int i = t; i < nseg; i += kScanThreads) {
+        const unsigned long long x = seg_sum[i];
+        all += x;
+        before += i < (int)blockIdx.x ? x : 0ull;
     }
-    const unsigned long long wtot = __shfl(wave_incl_scan_u64(lsum, lane), 63, 64);
-    if (lane == 0)
-        wsum[wave] = wtot;
-    __syncthreads();
-    unsigned long long carry = 0, total = 0;
-    for (int w = 0; w < kScanWaves; ++w) {
-        const unsigned long long x = wsum[w];
-        carry += w < wave ? x : 0ull;
-        total += x;
-    }
+    const unsigned long long total = block_sum_u64(all, scratch);
+    unsigned long long carry = block_sum_u64(before, scratch);
 
     const double tot = (double)total;
     const double two_d = 2.0 * (double)prm.d;
@@ -245,20 +270,25 @@ __global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* _
     Best best = {-2.0, (long long)V + 1};  // below every penalised utility
     double best_C = 0.0, best_R = 0.0, best_U = 0.0;
     bool feas = false;
-    for (int rb0 = r0; rb0 < r1; rb0 += 64 * TB) {
-        uint64_t kb[TB];
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int r = rb0 + 64 * u + lane;
-            kb[u] = r < r1 ? keys[r] : 0ull;
-        }
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-        const int r = rb0 + 64 * u + lane;
-        const unsigned long long cnt = kb[u] >> 32;
+    const int r0 = blockIdx.x * seg;
+    const int r1 = r0 + seg < V ? r0 + seg : V;
+    for (int rb = r0; rb < r1; rb += kScanThreads) {
+        const int r = rb + t;
+        const unsigned long long cnt = r < r1 ? (unsigned long long)(keys[r] >> 32) : 0ull;
+        // inclusive scan over the tile: within the wave, then the waves before this one
         const unsigned long long incl = wave_incl_scan_u64(cnt, lane);
-        const unsigned long long prefix = carry + incl;  // sum of the r+1 largest frequencies
-        carry += __shfl(incl, 63, 64);
+        __syncthreads();
+        if (lane == 63)
+            scratch[wave] = incl;
+        __syncthreads();
+        unsigned long long wbefore = 0, tile = 0;
+        for (int i = 0; i < kScanWaves; ++i) {
+            const unsigned long long x = scratch[i];
+            wbefore += i < wave ? x : 0ull;
+            tile += x;
+        }
+        const unsigned long long prefix = carry + wbefore + incl;  // sum of the r+1 largest frequencies
+        carry += tile;
         const long long k = (long long)r + 1;
         if (r < r1 && k >= prm.k_min && k <= prm.k_max) {
             const double C = (double)prefix / tot;
@@ -270,12 +300,10 @@ __global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* _
             const Best cand = {ok ? U : -1.0, k};
             if (beats(cand, best)) {
                 best = cand;
-                // C, R, U at the best k so far travel with it (reported below)
                 best_C = C;
                 best_R = R;
                 best_U = U;
             }
-        }
         }
     }
     if (feas)
@@ -287,13 +315,54 @@ __global__ void __launch_bounds__(kScanThreads) utility_kernel(const uint64_t* _
             best_s[t] = best_s[t + off];
         __syncthreads();
     }
-    // the thread whose own best is the overall best reports (k is unique to one thread)
-    if (best.k == best_s[0].k) {
-        out->k_star = best.k;
+    // the thread whose own best is the segment's best reports (a k belongs to one thread); a
+    // segment outside the range reports the initial value, which loses against everything
+    if (best.k == best_s[0].k && (best.k <= V || t == 0)) {
+        BlockBest bb;
+        bb.u = best.u;
+        bb.k = best.k;
+        bb.C = best_C;
+        bb.R = best_R;
+        bb.U = best_U;
+        bb.feasible = feas_s;
+        seg_best[blockIdx.x] = bb;
+    }
+}
+
+// pass 3: the best over the segments
+__global__ void __launch_bounds__(kSegBlocks) utility_final_kernel(const BlockBest* __restrict__ seg_best, int nseg,
+                                                                   const unsigned long long* __restrict__ seg_sum,
+                                                                   vt_selection* __restrict__ out)
+{
+    __shared__ Best best_s[kSegBlocks];
+    __shared__ int feas_s;
+    const int t = threadIdx.x;
+    if (t == 0)
+        feas_s = 0;
+    __syncthreads();
+    Best mine = {-3.0, (long long)1 << 62};
+    if (t < nseg) {
+        mine.u = seg_best[t].u;
+        mine.k = seg_best[t].k;
+        if (seg_best[t].feasible)
+            atomicOr(&feas_s, 1);
+    }
+    best_s[t] = mine;
+    __syncthreads();
+    for (int off = kSegBlocks / 2; off > 0; off >>= 1) {
+        if (t < off && beats(best_s[t + off], best_s[t]))
+            best_s[t] = best_s[t + off];
+        __syncthreads();
+    }
+    if (t < nseg && mine.k == best_s[0].k) {
+        unsigned long long total = 0;
+        for (int i = 0; i < nseg; ++i)
+            total += seg_sum[i];
+        out->k_star = mine.k;
         out->feasible = feas_s;
-        out->C = best_C;
-        out->R = best_R;
-        out->U = best_U;
+        out->C = seg_best[t].C;
+        out->R = seg_best[t].R;
+        out->U = seg_best[t].U;
         out->n_tokens = total;
     }
 }
@@ -307,52 +376,53 @@ __global__ void mark_kernel(const int32_t* __restrict__ rank_ids, const vt_selec
         mark[rank_ids[r]] = (r < sel->k_star) ? 1u : 0u;
 }
 
-// One workgroup; wave w owns a contiguous segment of ids, tiles of 64: a ballot of the marks
-// gives both the tile's count and every marked lane's position.
-__global__ void __launch_bounds__(kScanThreads) compact_kernel(const uint32_t* __restrict__ mark, int V,
+// Workgroup b owns the ids [b*seg, (b+1)*seg); a ballot of the marks gives a tile's count and
+// every marked lane's position.  First the counts per segment, then the writes.
+__global__ void __launch_bounds__(kScanThreads) mark_count_kernel(const uint32_t* __restrict__ mark, int V, int seg,
+                                                                  unsigned long long* __restrict__ seg_cnt)
+{
+    __shared__ unsigned long long scratch[kScanWaves];
+    const int v0 = blockIdx.x * seg;
+    const int v1 = v0 + seg < V ? v0 + seg : V;
+    unsigned long long cnt = 0;
+    for (int v = v0 + threadIdx.x; v < v1; v += kScanThreads)
+        cnt += mark[v] != 0u ? 1u : 0u;
+    cnt = block_sum_u64(cnt, scratch);
+    if (threadIdx.x == 0)
+        seg_cnt[blockIdx.x] = cnt;
+}
+
+__global__ void __launch_bounds__(kScanThreads) compact_kernel(const uint32_t* __restrict__ mark, int V, int seg,
+                                                               const unsigned long long* __restrict__ seg_cnt,
                                                                int32_t* __restrict__ token_ids)
 {
+    __shared__ unsigned long long scratch[kScanWaves];
     __shared__ unsigned int wcnt[kScanWaves];
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = t >> 6;
-    const int seg = ((V + kScanWaves - 1) / kScanWaves + 63) & ~63;
-    const int v0 = wave * seg < V ? wave * seg : V;
+    unsigned long long before = 0;
+    for (int i = t; i < (int)blockIdx.x; i += kScanThreads)
+        before += seg_cnt[i];
+    unsigned int pos = (unsigned int)block_sum_u64(before, scratch);
+    const int v0 = blockIdx.x * seg;
     const int v1 = v0 + seg < V ? v0 + seg : V;
-    constexpr int TB = 8;  // tiles fetched together
-    unsigned int cnt = 0;
-    for (int vb = v0; vb < v1; vb += 64 * TB) {
-        uint32_t mb[TB];
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int v = vb + 64 * u + lane;
-            mb[u] = v < v1 ? mark[v] : 0u;
+    for (int vb = v0; vb < v1; vb += kScanThreads) {
+        const int v = vb + t;
+        const bool m = v < v1 && mark[v] != 0u;
+        const unsigned long long b = __ballot(m);
+        __syncthreads();
+        if (lane == 0)
+            wcnt[wave] = (unsigned int)__popcll(b);
+        __syncthreads();
+        unsigned int wbefore = 0, tile = 0;
+        for (int i = 0; i < kScanWaves; ++i) {
+            wbefore += i < wave ? wcnt[i] : 0u;
+            tile += wcnt[i];
         }
-#pragma unroll
-        for (int u = 0; u < TB; ++u)
-            cnt += (unsigned int)__popcll(__ballot(mb[u] != 0u));
-    }
-    if (lane == 0)
-        wcnt[wave] = cnt;
-    __syncthreads();
-    unsigned int pos = 0;
-    for (int w = 0; w < wave; ++w)
-        pos += wcnt[w];
-    for (int vb = v0; vb < v1; vb += 64 * TB) {
-        uint32_t mb[TB];
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const int v = vb + 64 * u + lane;
-            mb[u] = v < v1 ? mark[v] : 0u;
-        }
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const bool m = mb[u] != 0u;
-            const unsigned long long b = __ballot(m);
-            if (m)
-                token_ids[pos + (unsigned int)__popcll(b & ((1ull << lane) - 1ull))] = vb + 64 * u + lane;
-            pos += (unsigned int)__popcll(b);
-        }
+        if (m)
+            token_ids[pos + wbefore + (unsigned int)__popcll(b & ((1ull << lane) - 1ull))] = v;
+        pos += tile;
     }
 }
 
@@ -373,7 +443,8 @@ SelectLayout select_layout(int64_t V)
     L.off_keys = 0;
     L.off_mark = up((size_t)L.N2 * sizeof(uint64_t));
     L.off_result = L.off_mark + up((size_t)V * sizeof(uint32_t));
-    L.off_err = L.off_result + 256;
+    L.off_seg = L.off_result + 256;
+    L.off_err = L.off_seg + up((size_t)kSegBlocks * (2 * sizeof(unsigned long long) + sizeof(BlockBest)));
     L.total = L.off_err + 256;
     return L;
 }
@@ -416,9 +487,18 @@ hipError_t launch_select(const int32_t* tokens, int64_t n, int V, const SelectPa
                                stride);
         hipLaunchKernelGGL(bitonic_local_kernel, dim3(chunks), dim3(kSortThreads), 0, s, keys, size, size);
     }
-    hipLaunchKernelGGL(utility_kernel, dim3(1), dim3(kScanThreads), 0, s, keys, V, prm, rank_ids, res);
+    // segments of whole 1024-rank tiles over at most kSegBlocks workgroups
+    int seg = ((V + kSegBlocks - 1) / kSegBlocks + kScanThreads - 1) / kScanThreads * kScanThreads;
+    const int nseg = (V + seg - 1) / seg;
+    unsigned long long* seg_sum = reinterpret_cast<unsigned long long*>(ws + L.off_seg);
+    unsigned long long* seg_cnt = seg_sum + kSegBlocks;
+    BlockBest* seg_best = reinterpret_cast<BlockBest*>(seg_cnt + kSegBlocks);
+    hipLaunchKernelGGL(rank_sums_kernel, dim3(nseg), dim3(kScanThreads), 0, s, keys, V, seg, rank_ids, seg_sum);
+    hipLaunchKernelGGL(utility_kernel, dim3(nseg), dim3(kScanThreads), 0, s, keys, V, seg, prm, seg_sum, seg_best);
+    hipLaunchKernelGGL(utility_final_kernel, dim3(1), dim3(kSegBlocks), 0, s, seg_best, nseg, seg_sum, res);
     hipLaunchKernelGGL(mark_kernel, dim3((V + 255) / 256), dim3(256), 0, s, rank_ids, res, mark, V);
-    hipLaunchKernelGGL(compact_kernel, dim3(1), dim3(kScanThreads), 0, s, mark, V, token_ids);
+    hipLaunchKernelGGL(mark_count_kernel, dim3(nseg), dim3(kScanThreads), 0, s, mark, V, seg, seg_cnt);
+    hipLaunchKernelGGL(compact_kernel, dim3(nseg), dim3(kScanThreads), 0, s, mark, V, seg, seg_cnt, token_ids);
     return hipGetLastError();
 }
 
