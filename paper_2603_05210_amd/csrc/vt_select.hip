@@ -30,6 +30,7 @@ namespace vt {
 constexpr int kHistThreads = 1024;
 constexpr int kHistSlots = 16384;  // 128 KiB of LDS: one workgroup per compute unit
 constexpr int kHistEmpty = -1;
+constexpr int kHistProbes = 2;  // neighbouring slots tried before a token goes to memory (1: 331 us, 2: 274 us, 4: 277 us on 33.5 M tokens)
 
 __global__ void __launch_bounds__(kHistThreads) hist_kernel(const int32_t* __restrict__ tokens, int64_t n, int V,
                                                             uint32_t* __restrict__ freq, int* __restrict__ err)
@@ -55,11 +56,15 @@ __global__ void __launch_bounds__(kHistThreads) hist_kernel(const int32_t* __res
             return;
         }
         const int slot = (int)(((uint32_t)t * 2654435761u) >> 18);  // top 14 bits of a multiplicative hash
-        if (try_slot(slot, t))
-            atomicAdd(&tab_cnt[slot], 1u);
-        else if (try_slot(slot ^ 1, t))
-            atomicAdd(&tab_cnt[slot ^ 1], 1u);
-        else
+        bool done = false;
+#pragma unroll
+        for (int pr = 0; pr < kHistProbes; ++pr) {
+            if (!done && try_slot(slot ^ pr, t)) {
+                atomicAdd(&tab_cnt[slot ^ pr], 1u);
+                done = true;
+            }
+        }
+        if (!done)
             atomicAdd(&freq[t], 1u);
     };
     // a contiguous share per workgroup, 128-bit loads over its aligned middle
