@@ -4,15 +4,22 @@
 A "step" is one draft step through the C ABI: vt_draft_head (projection over the draft
 vocabulary with fused softmax statistics and top-k, merge, d2t remap) on inputs already in
 HBM.  vt_build_subset is the one-time set-up per draft vocabulary (Section 2.1 of the paper)
-and is timed separately ("build_subset" in the output), not as part of a step.
+and is timed separately ("build_subset_us"), not as part of a step.
 
-Headline workload: the untrimmed baseline head at one row (H=2048, V=128256, k=10) -- the
-cost the paper's trimming attacks (Section 2.3: 2*d*V FLOPs = bytes of bf16 W per token).
-The other workloads (row counts 4 and 8, the V_draft sweep 4096..128256 at H=4096, the
-1024-row tree-drafting batch and the 512-row full-vocabulary batch) are reported in "sweep".
+Headline workload: the metric's own curve -- one row, H = 4096 (the paper's d), V_draft swept
+from 4096 to the full 128 256 (Section 2.3: the head costs 2*d*k FLOPs = bytes of bf16 W_sub
+per token); `value` is the full-vocabulary end of the curve, every other point, the three
+vocabulary sizes the paper itself selects (Sections 2.6 and 3.2), the 2048-wide heads and the
+two tree-drafting batches are in "sweep".
 
-Timing is "cold": calls rotate over enough distinct copies of W_sub that the footprint
-exceeds 1 GiB, so the 256 MB last-level cache cannot serve repeats.  Prints ONE JSON line.
+Protocol per workload, both flagged in the output:
+  cold   calls rotate over enough distinct copies of W_sub that the footprint exceeds 1 GiB,
+         so the 256 MB last-level cache cannot serve repeats (roofline fractions use this);
+  warm   the same W_sub every call (what a serving loop sees at small V_draft: a cache number).
+Each mode: `steps` back-to-back calls between one event pair (dense-loop mean, the figure the
+roofline fraction is computed from) and `steps` calls each between its own event pair (p10 /
+median / p90; these carry about 2 us of event overhead per call).  All events are recorded on
+the stream the kernels are launched on.  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -29,6 +36,8 @@ if str(ROOT) not in sys.path:
 
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix cores
+HEADLINE = "cfg2_Vd128256"
+PAPER_SIZES = (4380, 6521, 13264)   # function calling, NER (Section 3.2), general (Section 2.6)
 
 
 def parse_args():
@@ -37,7 +46,9 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-sweep", action="store_true", help="only the headline workload")
-    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline legs")
+    ap.add_argument("--no-warm", action="store_true", help="skip the warm (same W_sub every call) mode")
+    ap.add_argument("--no-percall", action="store_true", help="skip the per-call event pass (dense loop only)")
     ap.add_argument("--only", type=str, default=None, help="run a single named workload as the headline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference for scaling the "
@@ -50,17 +61,25 @@ def parse_args():
 
 
 def workloads():
+    """The headline first, then the rest of its curve, then the other configurations."""
     from paper_2603_05210_amd.synth import FULL_VOCAB as V
-    w = []
-    w.append(dict(name="cfg1_B1", H=2048, rows=1, Vd=V, k=10, peaked=0.0))
-    w.append(dict(name="cfg0", H=2048, rows=1, Vd=4096, k=1, peaked=0.0))
-    w.append(dict(name="cfg1_B4", H=2048, rows=4, Vd=V, k=10, peaked=0.0))
-    w.append(dict(name="cfg1_B8", H=2048, rows=8, Vd=V, k=10, peaked=0.0))
-    for vd in (4096, 8192, 16384, 32768, 65536, V):
+    w = [dict(name=HEADLINE, H=4096, rows=1, Vd=V, k=10, peaked=0.0)]
+    for vd in (4096, 8192, 16384, 32768, 65536):
         w.append(dict(name="cfg2_Vd%d" % vd, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
+    for vd in PAPER_SIZES:
+        w.append(dict(name="paper_Vd%d" % vd, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
+    w.append(dict(name="cfg0", H=2048, rows=1, Vd=4096, k=1, peaked=0.0))
+    for b in (1, 4, 8):
+        w.append(dict(name="cfg1_B%d" % b, H=2048, rows=b, Vd=V, k=10, peaked=0.0))
     w.append(dict(name="cfg3", H=4096, rows=1024, Vd=32000, k=8, peaked=0.0))
     w.append(dict(name="cfg4", H=4096, rows=512, Vd=V, k=16, peaked=0.05))
     return w
+
+
+def describe(w):
+    from paper_2603_05210_amd.synth import FULL_VOCAB as V
+    kind = "untrimmed head, identity d2t" if w["Vd"] == V else "Zipf(1.1)-ranked draft vocabulary of a %d-token head" % V
+    return "%s: rows=%d H=%d V_draft=%d k=%d (%s)" % (w["name"], w["rows"], w["H"], w["Vd"], w["k"], kind)
 
 
 def algorithmic(w):
@@ -69,6 +88,13 @@ def algorithmic(w):
     nbytes = 2 * H * Vd + 2 * R * H + 4 * k * R + 8 * k * R
     flops = 2 * R * H * Vd
     return nbytes, flops
+
+
+def percentile(sorted_vals, q):
+    if not sorted_vals:
+        return None
+    i = min(len(sorted_vals) - 1, max(0, int(round(q * (len(sorted_vals) - 1)))))
+    return sorted_vals[i]
 
 
 class Runner:
@@ -84,6 +110,10 @@ class Runner:
             self.W_host[H] = Wh
             self.W_dev[H] = self.torch.from_numpy(Wh.view(np.int16)).to(self.dev).view(self.torch.bfloat16)
         return self.W_host[H], self.W_dev[H]
+
+    def drop_W(self, H):
+        self.W_host.pop(H, None)
+        self.W_dev.pop(H, None)
 
     def prepare(self, w):
         import numpy as np
@@ -105,16 +135,17 @@ class Runner:
         nbytes = W_sub.numel() * 2
         n_copies = max(2, -(-(1 << 30) // nbytes))
         copies = [W_sub] + [W_sub.clone() for _ in range(n_copies - 1)]
-        ws = torch.empty(max(16, vt.vt_draft_head_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"])),
-                         dtype=torch.uint8, device=self.dev)
+        ws = vt.new_workspace(vt.vt_draft_head_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"]), self.dev)
         out_ids = torch.empty((w["rows"], w["k"]), dtype=torch.int32, device=self.dev)
         out_lp = torch.empty((w["rows"], w["k"]), dtype=torch.float32, device=self.dev)
         return dict(ids=ids, h=h, h_dev=h_dev, d2t=d2t, copies=copies, ws=ws, out_ids=out_ids, out_lp=out_lp,
                     build_ms=build_ms, n_copies=n_copies)
 
-    def time_steps(self, w, st, steps, warmup):
+    def time_mode(self, w, st, steps, warmup, cold, percall):
+        """Dense-loop mean and per-call percentiles of one mode (cold: rotating W_sub copies)."""
         torch, vt = self.torch, self.vt
-        copies, n = st["copies"], len(st["copies"])
+        copies = st["copies"] if cold else st["copies"][:1]
+        n = len(copies)
 
         def step(i):
             vt.vt_draft_head(st["h_dev"], copies[i % n], st["d2t"], w["k"], st["out_ids"], st["out_lp"], st["ws"])
@@ -129,52 +160,58 @@ class Runner:
             step(warmup + i)
         e1.record()
         torch.cuda.synchronize()
-        wall_ms = (time.perf_counter() - t0) * 1e3
-        dev_ms = e0.elapsed_time(e1)
-        # second pass: HIP events around the projection kernel alone, on the same stream
-        vt.vt_kernel_timing_enable(True)
-        for i in range(steps):
-            step(warmup + i)
-        torch.cuda.synchronize()
-        n_l, k_ms = vt.vt_kernel_timing_read()
-        vt.vt_kernel_timing_enable(False)
-        return dict(ms_per_step=max(wall_ms, dev_ms) / steps, dev_ms_per_step=dev_ms / steps,
-                    kernel_ms=k_ms / max(n_l, 1), kernel_launches=n_l)
+        wall_us = (time.perf_counter() - t0) * 1e6 / steps
+        dense_us = e0.elapsed_time(e1) * 1e3 / steps
+        out = dict(mode="cold" if cold else "warm", dense_loop_us=dense_us, wall_us=wall_us,
+                   us_per_step=max(dense_us, wall_us))
+        if percall:
+            evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+            for i, (a, b) in enumerate(evs):
+                a.record()
+                step(warmup + i)
+                b.record()
+            torch.cuda.synchronize()
+            v = sorted(a.elapsed_time(b) * 1e3 for a, b in evs)
+            out.update(percall_p10_us=percentile(v, 0.10), percall_median_us=percentile(v, 0.50),
+                       percall_p90_us=percentile(v, 0.90), percall_calls=steps)
+        return out
 
 
-def report(w, st, t):
+def report(w, st, cold, warm):
     nbytes, flops = algorithmic(w)
     regime = "hbm" if w["rows"] <= 16 else "mfma"
-    k_s = t["kernel_ms"] * 1e-3
-    gbs = nbytes / k_s / 1e9
-    tfl = flops / k_s / 1e12
+    t_s = cold["us_per_step"] * 1e-6   # dense-loop device time per step (wall clock if that is larger)
+    gbs = nbytes / t_s / 1e9
+    tfl = flops / t_s / 1e12
     if regime == "hbm":
         roof = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS, traffic=None)
     else:
         roof = dict(bound="mfma", achieved=tfl, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=tfl / MFMA_BF16_PEAK_TFLOPS, traffic=None)
-    roof["kernel"] = "gemv_head_kernel" if regime == "hbm" else "gemm_head_kernel"
-    roof["kernel_us"] = t["kernel_ms"] * 1e3
+    roof["kernel"] = "streaming head kernel (whole step)" if regime == "hbm" else "gemm_head_kernel + merge_kernel (whole step)"
+    roof["from"] = "cold dense-loop time per step"
     roof["algorithmic_bytes"] = nbytes
     roof["algorithmic_flops"] = flops
-    return dict(workload=w["name"], rows=w["rows"], H=w["H"], V_draft=w["Vd"], k=w["k"],
-                us_per_step=t["ms_per_step"] * 1e3, device_us_per_step=t["dev_ms_per_step"] * 1e3,
-                step_GBps=nbytes / (t["ms_per_step"] * 1e-3) / 1e9, step_TFLOPs=flops / (t["ms_per_step"] * 1e-3) / 1e12,
-                build_subset_us=st["build_ms"] * 1e3, w_sub_copies=st["n_copies"], roofline=roof)
+    roof["traffic"] = recorded_traffic(w["name"])
+    rep = dict(workload=w["name"], rows=w["rows"], H=w["H"], V_draft=w["Vd"], k=w["k"],
+               us_per_step=cold["us_per_step"], cold=cold, warm=warm,
+               build_subset_us=st["build_ms"] * 1e3, w_sub_copies=st["n_copies"], roofline=roof)
+    if warm is not None:
+        rep["warm_effective_GBps"] = nbytes / (warm["us_per_step"] * 1e-6) / 1e9   # may exceed HBM peak: served by the last-level cache
+    return rep
 
 
-def cpu_baseline(runner, w, st):
-    """The CPU oracle, as it stands, on the headline workload (bounded to ~10-30 s)."""
+def cpu_baseline(runner, w, st, budget_s):
+    """The CPU oracle, as it stands, on a bounded sample of the workload's rows."""
     from oracle import vt_oracle as vo
     Wh, _ = runner.full_W(w["H"])
     ids = st["ids"]
     W_sub = Wh if len(ids) == Wh.shape[0] else Wh[ids]
     rows = st["h"].shape[0]
-    # bounded sample: at most 8 rows of the batch, repeated until ~10 s have passed
-    r_use = min(rows, 8)
+    r_use = min(rows, 4)
     h = st["h"][:r_use]
     reps, t_total = 0, 0.0
-    while t_total < 10.0 and reps < 5000:
+    while t_total < budget_s and reps < 5000:
         t0 = time.perf_counter()
         vo.draft_head(h, W_sub, ids, w["k"], want_logits=False)
         t_total += time.perf_counter() - t0
@@ -191,7 +228,7 @@ def kernel_source_hash():
     import hashlib
     h = hashlib.sha256()
     for f in sorted((ROOT / "paper_2603_05210_amd" / "csrc").glob("*")):
-        if f.suffix in (".hip", ".h") and not f.name.startswith(("vt_select", "vt_coverage")):
+        if f.suffix in (".hip", ".h", ".cpp") and not f.name.startswith(("vt_select", "vt_coverage")):
             h.update(f.name.encode())
             h.update(f.read_bytes())
     return h.hexdigest()
@@ -304,26 +341,35 @@ def main():
     if args.only:
         wl = [w for w in wl if w["name"] == args.only]
         assert wl, "unknown workload"
-    head = wl[0]
-    st = runner.prepare(head)
-    torch.cuda.synchronize()
-    t = runner.time_steps(head, st, args.steps, args.warmup)
-    torch.cuda.synchronize()
-    head_rep = report(head, st, t)
-    head_rep["roofline"]["traffic"] = recorded_traffic(head["name"])
-    cpu = None if args.no_cpu else cpu_baseline(runner, head, st)
-    del st
-    sweep = []
-    if not args.no_sweep and not args.only:
-        for w in wl[1:]:
-            s = runner.prepare(w)
-            steps = max(20, min(args.steps, 100))
-            sweep.append(report(w, s, runner.time_steps(w, s, steps, min(args.warmup, 10))))
-            del s
-            torch.cuda.empty_cache()
+    if args.no_sweep:
+        wl = wl[:1]
+    # group by hidden size so that only one full matrix is resident at a time
+    order = [wl[0]] + sorted(wl[1:], key=lambda w: (w["H"] != wl[0]["H"], w["H"]))
 
+    reports, cpus = {}, {}
+    for n, w in enumerate(order):
+        if n > 0 and w["H"] != order[n - 1]["H"]:
+            runner.drop_W(order[n - 1]["H"])
+            torch.cuda.empty_cache()
+        st = runner.prepare(w)
+        torch.cuda.synchronize()
+        steps, warmup = (args.steps, args.warmup) if n == 0 else (max(20, args.steps), max(5, args.warmup))
+        cold = runner.time_mode(w, st, steps, warmup, True, not args.no_percall)
+        warm = None if args.no_warm else runner.time_mode(w, st, steps, warmup, False, not args.no_percall)
+        reports[w["name"]] = report(w, st, cold, warm)
+        if not args.no_cpu:
+            cpus[w["name"]] = cpu_baseline(runner, w, st, 8.0 if n == 0 else 1.0)
+            reports[w["name"]]["cpu_baseline"] = cpus[w["name"]]
+        del st
+        torch.cuda.empty_cache()
+
+    head = wl[0]
+    head_rep = reports[head["name"]]
+    sweep = [reports[w["name"]] for w in wl[1:]]
     selector = None
     if not args.no_sweep and not args.only:
+        runner.drop_W(order[-1]["H"])
+        torch.cuda.empty_cache()
         selector = selector_bench(torch, vt, synth, dev, with_cpu=not args.no_cpu)
 
     out = {
@@ -338,13 +384,15 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic (seeded N(0,0.02) W, N(0,1) h, Zipf(1.1)-ranked subsets); cold: rotating W_sub copies > 1 GiB",
-        "config": {"workload": "%s: rows=%d H=%d V_draft=%d k=%d (untrimmed baseline head, identity d2t)"
-                               % (head["name"], head["rows"], head["H"], head["Vd"], head["k"]),
-                   "device_us_per_step": head_rep["device_us_per_step"],
+        "data": "synthetic (seeded N(0,0.02) W, N(0,1) h, Zipf(1.1)-ranked subsets); value = cold: rotating W_sub copies > 1 GiB",
+        "config": {"workload": describe(head), "mode": "cold",
+                   "percall_median_us": head_rep["cold"].get("percall_median_us"),
+                   "percall_p10_us": head_rep["cold"].get("percall_p10_us"),
+                   "percall_p90_us": head_rep["cold"].get("percall_p90_us"),
+                   "warm_us_per_step": None if head_rep["warm"] is None else head_rep["warm"]["us_per_step"],
                    "build_subset_us": head_rep["build_subset_us"]},
         "roofline": head_rep["roofline"],
-        "cpu_baseline": cpu,
+        "cpu_baseline": cpus.get(head["name"]),
         "sweep": sweep,
         "selector": selector,
     }

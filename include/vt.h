@@ -88,6 +88,17 @@ vt_status vt_validate_draft_head_args(const void *h, int64_t rows, int64_t H, co
  * A pure function of its arguments: it does not depend on the device. */
 size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k);
 
+/*
+ * One-time preparation of a workspace buffer for vt_draft_head: zeroes its 256-byte header, which
+ * holds the arrival counter of the single-launch merge of the one- and two-row steps (Section
+ * 2.3's head is one kernel there; the last workgroup to finish merges the partial results).
+ * Every call leaves the counter at zero again, so one initialisation serves any number of calls
+ * of any shapes; initialise again only if something else has written to the buffer.  Enqueues
+ * one small kernel on `stream` (safe to record into a graph); VT_ERR_NULL / VT_ERR_WORKSPACE
+ * (fewer than 256 bytes) / VT_ERR_ALIGN / VT_ERR_DEVICE.
+ */
+vt_status vt_draft_head_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
+
 /* Which kernel family serves this shape: 0 = streaming row-split kernels (memory bound,
  * rows <= 16), 1 = bf16 MFMA thin GEMM (rows > 16); -1 on invalid arguments. */
 int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
@@ -103,13 +114,12 @@ int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
  *   d2t             device, [V_draft] int32
  *   out_target_ids  device, [rows,k] int32       out_logprobs  device, [rows,k] fp32
  *   workspace       device, >= vt_draft_head_workspace_bytes(...) bytes, 16-byte aligned,
- *                   contents need not be initialised and are clobbered
+ *                   initialised once by vt_draft_head_workspace_init; contents are clobbered
  *
- * Asynchronous on `stream`: no allocation, no synchronisation, no host read.  Concurrent
- * calls must not share a workspace, and at most 1024 one- or two-row calls may be in flight at
- * once across streams (their single-launch merge keeps one arrival counter per call in a
- * table of that size; calls on one stream run in order and are not limited).  The logits are
- * never written to memory.
+ * Asynchronous on `stream`: no allocation, no synchronisation, no host read.  Calls that may
+ * overlap in time (different streams) must not share a workspace: it holds the call's partial
+ * results and the arrival counter of its single-launch merge.  Calls on one stream run in order
+ * and may share one.  The logits are never written to memory.
  */
 vt_status vt_draft_head(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
                         const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
@@ -124,18 +134,6 @@ vt_status vt_draft_head_debug(const uint16_t *h, int64_t rows, int64_t H, const 
                               const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
                               float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream,
                               float *logits_out, float *lse_out);
-
-/*
- * Timing of the dominant kernel, for roofline reporting.  When enabled, every later
- * vt_draft_head call records a HIP event pair around its projection kernel (the streaming
- * dot product or the MFMA GEMM, not the small merge kernel) on the call's own stream.
- * vt_kernel_timing_read waits for the recorded events, returns the number of timed launches
- * and their total duration in milliseconds, and resets the counters.  Off by default; at most
- * VT_TIMING_MAX_EVENTS launches are kept between reads.
- */
-#define VT_TIMING_MAX_EVENTS 4096
-vt_status vt_kernel_timing_enable(int on);
-vt_status vt_kernel_timing_read(int *launches, double *total_ms);
 
 /*
  * Draft-vocabulary size selection (Section 2, Eq. 1-5).  From a stream of token ids (the

@@ -26,8 +26,8 @@ STATUS_NAMES = {
 EXPORTS = (
     "vt_version", "vt_status_str", "vt_build_subset", "vt_check_token_ids_host",
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
-    "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug", "vt_kernel_timing_enable",
-    "vt_kernel_timing_read", "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
+    "vt_draft_head_workspace_init", "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug",
+    "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
     "vt_select_vocab", "vt_build_t2d", "vt_coverage_workspace_bytes", "vt_coverage",
 )
 
@@ -69,10 +69,8 @@ def lib() -> ctypes.CDLL:
         L.vt_draft_head.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p]
         L.vt_draft_head_debug.restype = i32
         L.vt_draft_head_debug.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p]
-        L.vt_kernel_timing_enable.restype = i32
-        L.vt_kernel_timing_enable.argtypes = [i32]
-        L.vt_kernel_timing_read.restype = i32
-        L.vt_kernel_timing_read.argtypes = [ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_double)]
+        L.vt_draft_head_workspace_init.restype = i32
+        L.vt_draft_head_workspace_init.argtypes = [p, sz, p]
         f64 = ctypes.c_double
         L.vt_select_vocab_workspace_bytes.restype = sz
         L.vt_select_vocab_workspace_bytes.argtypes = [i64]
@@ -150,16 +148,33 @@ def vt_build_subset(full_W: torch.Tensor, token_ids: torch.Tensor, W_sub_out: to
     return W_sub_out, d2t_out
 
 
+def vt_draft_head_workspace_init(workspace: torch.Tensor) -> torch.Tensor:
+    """Prepare a freshly allocated workspace buffer for vt_draft_head (zeroes its header)."""
+    if not workspace.is_cuda or not workspace.is_contiguous():
+        raise TypeError("workspace must be a contiguous device tensor")
+    with torch.cuda.device(workspace.device):
+        st = lib().vt_draft_head_workspace_init(workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                                _stream_ptr(workspace))
+    if st != VT_OK:
+        raise VtError(st, "vt_draft_head_workspace_init")
+    return workspace
+
+
+def new_workspace(nbytes: int, device) -> torch.Tensor:
+    """A device buffer of at least `nbytes` bytes, initialised for vt_draft_head."""
+    return vt_draft_head_workspace_init(torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device))
+
+
 class Workspace:
-    """A reusable device buffer sized by vt_draft_head_workspace_bytes."""
+    """A reusable device buffer sized by vt_draft_head_workspace_bytes (initialised when it grows)."""
 
     def __init__(self, device):
         self.device = device
-        self.buf = torch.empty(0, dtype=torch.uint8, device=device)
+        self.buf = None
 
     def get(self, nbytes: int) -> torch.Tensor:
-        if self.buf.numel() < nbytes:
-            self.buf = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        if self.buf is None or self.buf.numel() < nbytes:
+            self.buf = new_workspace(nbytes, self.device)
         return self.buf
 
 
@@ -185,7 +200,7 @@ def vt_draft_head(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor, k: in
         out_logprobs = torch.empty((rows, k), dtype=torch.float32, device=dev)
     need = vt_draft_head_workspace_bytes(rows, H, Vd, k)
     if workspace is None:
-        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+        workspace = new_workspace(need, dev)
     L = lib()
     with torch.cuda.device(dev):
         if logits_out is None and lse_out is None:
@@ -201,22 +216,6 @@ def vt_draft_head(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor, k: in
     if st != VT_OK:
         raise VtError(st, "vt_draft_head")
     return out_target_ids, out_logprobs
-
-
-def vt_kernel_timing_enable(on: bool) -> None:
-    st = lib().vt_kernel_timing_enable(1 if on else 0)
-    if st != VT_OK:
-        raise VtError(st, "vt_kernel_timing_enable")
-
-
-def vt_kernel_timing_read():
-    """(launches, total milliseconds) of the projection kernel since the last read."""
-    n = ctypes.c_int(0)
-    ms = ctypes.c_double(0.0)
-    st = lib().vt_kernel_timing_read(ctypes.byref(n), ctypes.byref(ms))
-    if st != VT_OK:
-        raise VtError(st, "vt_kernel_timing_read")
-    return int(n.value), float(ms.value)
 
 
 class VtSelection(ctypes.Structure):

@@ -20,10 +20,13 @@ FLAGS = [
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-I", str(ROOT / "include"), "-I", str(CSRC),
 ]
+CXX = os.environ.get("CXX", "g++")
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra", "-I", str(ROOT / "include"), "-I", str(CSRC)]
 
 
 def sources():
-    return sorted(CSRC.glob("*.hip"))
+    """Kernels and device-facing entry points (.hip) and the pure host part (.cpp)."""
+    return sorted(CSRC.glob("*.hip")) + sorted(CSRC.glob("*.cpp"))
 
 
 def build(verbose: bool = False) -> Path:
@@ -33,7 +36,10 @@ def build(verbose: bool = False) -> Path:
 
     def compile_one(src: Path) -> Path:
         obj = OBJ / (src.stem + ".o")
-        cmd = [HIPCC, *FLAGS, "-c", str(src), "-o", str(obj)]
+        if src.suffix == ".cpp":  # pure host code: the host compiler, no device pass
+            cmd = [CXX, *HOST_FLAGS, "-c", str(src), "-o", str(obj)]
+        else:
+            cmd = [HIPCC, *FLAGS, "-c", str(src), "-o", str(obj)]
         r = subprocess.run(cmd, capture_output=True, text=True)
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
         if r.returncode != 0:

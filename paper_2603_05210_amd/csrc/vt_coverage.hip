@@ -5,7 +5,8 @@
 // index, used to mask and remap target tokens when the draft is trained or checked).  Section
 // 5.1 / Table 4 measure a vocabulary on generated text by two ratios: the share of token
 // occurrences it covers (Eq. 2 evaluated on that stream) and the share of distinct tokens.
-// Everything here is integer work; the two ratios are one double division each.
+// Everything here is integer work; the two ratios are one double division each, taken on the
+// device by the call's last kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -164,6 +165,14 @@ __global__ void __launch_bounds__(kCovThreads) unique_kernel(const uint32_t* __r
     }
 }
 
+// The table's two ratios (one IEEE double division each), written behind the three counters.
+__global__ void coverage_ratio_kernel(const unsigned long long* __restrict__ counters, unsigned long long n,
+                                      double* __restrict__ ratios)
+{
+    ratios[0] = (double)counters[0] / (double)n;
+    ratios[1] = (double)counters[2] / (double)counters[1];
+}
+
 CoverageLayout coverage_layout(int64_t V)
 {
     CoverageLayout L;
@@ -222,6 +231,8 @@ hipError_t launch_coverage(const int32_t* tokens, int64_t n, const int32_t* t2d,
     if (ub > 256)
         ub = 256;
     hipLaunchKernelGGL(unique_kernel, dim3(ub), dim3(kCovThreads), 0, s, seen, t2d, V, counters);
+    hipLaunchKernelGGL(coverage_ratio_kernel, dim3(1), dim3(1), 0, s, counters, (unsigned long long)n,
+                       reinterpret_cast<double*>(counters + 4));
     return hipGetLastError();
 }
 

@@ -20,37 +20,6 @@
 
 namespace vt {
 
-// ---- tile shapes ----
-// tile 0: 128 tokens x 128 rows, 4 waves (2x2), 64x64 per wave: any k <= 64, any H % 8 == 0.
-// tile 1: 256 tokens x 256 rows, 8 waves (2x4), 128x64 per wave (128 accumulators, two waves per
-//         SIMD hide each other's LDS / barrier / epilogue stalls; operand traffic from L2 is that
-//         of the largest tile): k <= 16, H % 64 == 0.
-// tile 2: 32 tokens x 128 rows, 4 waves (1x4), 32x32 per wave: for at most 128 rows over a narrow
-//         vocabulary, where 128-token tiles would leave most compute units without a workgroup
-//         (the shape is bound by reading W_sub once, not by the matrix cores).
-struct TileInfo {
-    int BMV, BNR, parts_per_vtile;
-};
-static const TileInfo kTiles[] = {{128, 128, 4}, {256, 256, 4}, {32, 128, 2}};
-
-void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile)
-{
-    BMV = kTiles[tile].BMV;
-    BNR = kTiles[tile].BNR;
-    parts_per_vtile = kTiles[tile].parts_per_vtile;
-}
-
-int gemm_pick_tile(int rows, int H, int Vd, int KP)
-{
-    // one row tile and fewer 128-token tiles than three quarters of the compute units: narrow tiles
-    if (rows <= 128 && (Vd + 127) / 128 < 192)
-        return 2;
-    // the large tile has no K-tail variant and no room for long candidate lists
-    if (KP > 16 || rows <= 128 || (H % 64) != 0)
-        return 0;
-    return 1;
-}
-
 hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s)
 {
     GemmArgs ga;

@@ -34,27 +34,24 @@ struct GemvArgs {
     float2* part_stat;
     float* logits_out;
     // fused final merge (done by the last workgroup to finish) -- used when `fused` is set
-    int fused, ticket_slot;
+    int fused;
+    unsigned int* arrive;  // this call's arrival counter (workspace header), zero between calls
     const int32_t* d2t;
     int32_t* out_ids;
     float* out_logp;
     float* lse_out;
 };
 
-// Arrival counters for the fused merge, one per in-flight call (the host hands out slots
-// round-robin); zero when idle: the last workgroup of a call puts its slot back to zero.
-// Calls on one stream run in order and may reuse a slot freely; across streams at most
-// kTicketSlots fused calls may be in flight at once.
+// The arrival counter of the fused merge lives in the header of the call's own workspace (which
+// concurrent calls never share): zero between calls, the last workgroup of a call puts it back.
 //
 // No cache-wide fences are used: the partial results are a few hundred bytes per workgroup and
 // travel through device-coherent accesses (relaxed agent-scope atomics: they bypass the
 // per-XCD caches), ordered by "stores acknowledged -> workgroup barrier -> ticket".
-constexpr int kTicketSlots = 1024;
 __device__ __forceinline__ void st_dev(float* p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ void st_dev(int* p, int v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
-static __device__ unsigned int g_ticket[kTicketSlots];
 
 // Final merge by the last workgroup: the partial lists of every row are fetched into LDS (all
 // threads, coalesced), 256 threads per hidden-state row reduce the row's softmax partials, then
@@ -246,7 +243,7 @@ __device__ __forceinline__ void block_tail(const GemvArgs& a, u32x4* smem, const
     __syncthreads();
     if (tid == 0) {
         const unsigned int t =
-            __hip_atomic_fetch_add(&g_ticket[a.ticket_slot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_last = (t == gridDim.x - 1) ? 1 : 0;
     }
     __syncthreads();
@@ -261,7 +258,7 @@ __device__ __forceinline__ void block_tail(const GemvArgs& a, u32x4* smem, const
     default: fused_final_merge<16>(a, lds, tid); break;
     }
     if (tid == 0)
-        __hip_atomic_store(&g_ticket[a.ticket_slot], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int NR, int J, bool DOT2>
@@ -604,8 +601,7 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.part_stat = a.part_stat;
     ga.logits_out = a.logits_out;
     ga.fused = p.fused;
-    static std::atomic<unsigned int> next_slot{0};
-    ga.ticket_slot = p.fused ? (int)(next_slot.fetch_add(1u) % (unsigned int)kTicketSlots) : 0;
+    ga.arrive = a.arrive;
     ga.d2t = a.d2t;
     ga.out_ids = a.out_ids;
     ga.out_logp = a.out_logp;

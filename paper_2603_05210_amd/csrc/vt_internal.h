@@ -6,40 +6,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include "vt_plan.h"
+
 namespace vt {
-
-// Streaming regime (rows <= kGemvMaxRows): workgroups of kGemvThreads threads, each wave
-// streams groups of J consecutive W_sub rows.
-constexpr int kGemvMaxRows = 16;
-constexpr int kGemvThreads = 1024;
-constexpr int kGemvWaves = kGemvThreads / 64;
-constexpr int kGemvMaxRowsPerBlock = 512;  // W_sub rows one workgroup may own (8 logits per lane at the end)
-constexpr int kGemvTargetBlocks = 256;     // one workgroup per compute unit of an MI355X
-constexpr int kGemvLdsLimit = 160 * 1024;
-constexpr int kMergeThreads = 256;
-
-struct Plan {
-    int regime;  // 0 streaming dot product, 1 MFMA GEMM
-    int rows, H, Vd, k;
-    int KP;      // list length carried in the kernels: k rounded up to a power of two
-    // streaming regime
-    int NR;      // rows rounded up to a power of two
-    int J;       // W_sub rows a wave reduces together
-    int rpb;     // W_sub rows per workgroup
-    int fused;   // the streaming kernel's last workgroup also does the final merge
-    int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
-    int ks;      // its slices of the hidden dimension per 16-row group (narrow ranges: keeps 16 waves busy)
-    // GEMM regime
-    int tile;    // index into the table of tile shapes
-    int n_vtiles, n_rtiles;
-    // both
-    int blocks;  // workgroups of the projection kernel
-    int P;       // partial results per row handed to the merge kernel
-    size_t off_val, off_idx, off_stat, total_bytes;
-};
-
-// Fills `p`; returns false when the shape is not servable (caller has validated ranges).
-bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p);
 
 struct HeadArgs {
     const uint16_t* h;
@@ -47,6 +16,7 @@ struct HeadArgs {
     const int32_t* d2t;
     int32_t* out_ids;
     float* out_logp;
+    unsigned int* arrive;  // arrival counter in the workspace header
     float* part_val;   // [rows][P][KP]
     int32_t* part_idx; // [rows][P][KP]
     float2* part_stat; // [rows][P]  (max, sum exp(z - max))
@@ -78,12 +48,9 @@ VT_DECL_GEMM_KP(64)
 hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s);
+hipError_t launch_clear_words(uint32_t* p, int n, hipStream_t s);
 hipError_t launch_check_ids(const int32_t* ids, int Vd, int V, uint32_t* bitmap, int* err, hipStream_t s);
 hipError_t launch_gather(const uint16_t* W, int H, const int32_t* ids, int Vd, uint16_t* W_sub, int32_t* d2t,
                          hipStream_t s);
-
-// GEMM tile shapes (vocab x rows per workgroup) and their partial counts; defined with the kernel.
-int gemm_pick_tile(int rows, int H, int Vd, int KP);
-void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile);
 
 }  // namespace vt

@@ -257,6 +257,21 @@ hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Zeroes n 32-bit words (workspace header); a kernel rather than a memset so that a caller may
+// record it into a graph.
+__global__ void clear_words_kernel(uint32_t* __restrict__ p, int n)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n)
+        p[i] = 0u;
+}
+
+hipError_t launch_clear_words(uint32_t* p, int n, hipStream_t s)
+{
+    hipLaunchKernelGGL(clear_words_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------ subset construction
 
 // err bit 0: an id outside [0,V); bit 1: an id seen twice.  bitmap has ceil(V/32) zeroed words.

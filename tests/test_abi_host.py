@@ -105,8 +105,13 @@ def test_regime_and_workspace_query(rows, H, Vd, k, regime):
     assert vt.vt_draft_head_regime(rows, H + 1, Vd, k) == -1
 
 
-def test_timing_read_rejects_null():
-    assert vt.lib().vt_kernel_timing_read(None, None) == 1
+def test_workspace_init_argument_validation():
+    f = vt.lib().vt_draft_head_workspace_init
+    assert f(None, 4096, None) == 1
+    assert f(FAKE, 255, None) == 6
+    assert f(FAKE + 4, 4096, None) == 7
+    # every workspace size includes the header the call initialises
+    assert vt.vt_draft_head_workspace_bytes(1, 64, 8, 1) >= 256 + 256
 
 
 def test_select_vocab_argument_validation():

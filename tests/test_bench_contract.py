@@ -1,5 +1,5 @@
 """Host-only checks of bench.py's contract: it refuses more than one GPU with a message, its
-workload list is the five configurations, and its algorithmic byte / FLOP counts are the closed
+workload list is the five configurations (plus the vocabulary sizes the paper selects), and its algorithmic byte / FLOP counts are the closed
 forms (the head's FLOPs are the paper's 2 d k per row, Section 2.3 / Table 1)."""
 import subprocess
 import sys
@@ -19,7 +19,9 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 def test_workloads_are_the_five_configurations():
     wl = {w["name"]: w for w in bench.workloads()}
-    assert bench.workloads()[0]["name"] == "cfg1_B1"          # the headline comes first
+    assert bench.workloads()[0]["name"] == "cfg2_Vd128256"    # the headline (the metric's own curve) comes first
+    assert bench.workloads()[0]["H"] == 4096 and bench.workloads()[0]["rows"] == 1
+    assert sorted(w["Vd"] for n, w in wl.items() if n.startswith("paper_")) == [4380, 6521, 13264]  # Sections 2.6, 3.2
     assert {n for n in wl if n.startswith("cfg1_")} == {"cfg1_B1", "cfg1_B4", "cfg1_B8"}
     assert sorted(w["Vd"] for n, w in wl.items() if n.startswith("cfg2_")) == [4096, 8192, 16384, 32768, 65536, synth.FULL_VOCAB]
     c = synth.CONFIGS
@@ -38,3 +40,15 @@ def test_algorithmic_counts_are_the_closed_forms():
     nbytes, flops = bench.algorithmic(w)
     assert flops == 2 * 1024 * 4096 * 32000 and nbytes == 2 * 4096 * 32000 + 2 * 1024 * 4096 + 12 * 8 * 1024
     assert bench.HBM_PEAK_GBS == 8000.0 and bench.MFMA_BF16_PEAK_TFLOPS == 2500.0
+
+
+def test_workload_description_follows_the_selected_workload():
+    wl = {w["name"]: w for w in bench.workloads()}
+    assert "untrimmed" in bench.describe(wl["cfg2_Vd128256"]) and "V_draft=128256" in bench.describe(wl["cfg2_Vd128256"])
+    assert "untrimmed" not in bench.describe(wl["cfg2_Vd4096"]) and "V_draft=4096" in bench.describe(wl["cfg2_Vd4096"])
+
+
+def test_percentile_helper():
+    v = sorted(float(x) for x in range(101))
+    assert bench.percentile(v, 0.5) == 50.0 and bench.percentile(v, 0.1) == 10.0 and bench.percentile(v, 0.9) == 90.0
+    assert bench.percentile([], 0.5) is None and bench.percentile([3.0], 0.9) == 3.0
