@@ -126,6 +126,25 @@ vt_status vt_draft_head(const uint16_t *h, int64_t rows, int64_t H, const uint16
                         float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * vt_draft_head for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same arguments,
+ * same kernels and same results as vt_draft_head, but the partial results and the arrival
+ * counter live in a device-resident array of VT_STATIC_SCRATCH_BYTES bytes that is part of the
+ * library image (every GPU the library runs on holds one copy until the process ends).  The call
+ * allocates and frees nothing and never synchronises.
+ *   - VT_ERR_WORKSPACE when vt_draft_head_workspace_bytes(rows, H, V_draft, k) exceeds
+ *     VT_STATIC_SCRATCH_BYTES (nothing is launched); every other code as vt_draft_head.
+ *   - All calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ *     (different streams, different host threads) race and give undefined results; calls on one
+ *     stream run in order and are safe.  The array keeps the previous call's partial results;
+ *     every call overwrites what it reads and leaves the arrival counter at zero.
+ */
+#define VT_STATIC_SCRATCH_BYTES (40u << 20)
+vt_status vt_draft_head_static(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
+                               const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
+                               float *out_logprobs, void *stream);
+
+/*
  * Test hook, same computation through the same kernels, which additionally store
  *   logits_out  device, [rows,V_draft] fp32 (may be NULL)
  *   lse_out     device, [rows] fp32         (may be NULL)

@@ -27,6 +27,7 @@ EXPORTS = (
     "vt_version", "vt_status_str", "vt_build_subset", "vt_check_token_ids_host",
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
     "vt_draft_head_workspace_init", "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug",
+    "vt_draft_head_static",
     "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
     "vt_select_vocab", "vt_build_t2d", "vt_coverage_workspace_bytes", "vt_coverage",
 )
@@ -67,6 +68,8 @@ def lib() -> ctypes.CDLL:
         L.vt_draft_head_regime.argtypes = [i64, i64, i64, i32]
         L.vt_draft_head.restype = i32
         L.vt_draft_head.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p]
+        L.vt_draft_head_static.restype = i32
+        L.vt_draft_head_static.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p]
         L.vt_draft_head_debug.restype = i32
         L.vt_draft_head_debug.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p]
         L.vt_draft_head_workspace_init.restype = i32
@@ -215,6 +218,32 @@ def vt_draft_head(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor, k: in
                                        None if lse_out is None else lse_out.data_ptr())
     if st != VT_OK:
         raise VtError(st, "vt_draft_head")
+    return out_target_ids, out_logprobs
+
+
+VT_STATIC_SCRATCH_BYTES = 40 << 20
+
+
+def vt_draft_head_static(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor, k: int,
+                         out_target_ids: torch.Tensor, out_logprobs: torch.Tensor):
+    """vt_draft_head without a workspace argument and without any allocation: outputs must be
+    passed in; partial results live in the library's device-resident scratch array."""
+    _dev16(h, "h")
+    _dev16(W_sub, "W_sub")
+    _devi32(d2t, "d2t")
+    _devi32(out_target_ids, "out_target_ids")
+    rows, H = h.shape
+    Vd, H2 = W_sub.shape
+    if H2 != H or d2t.shape[0] != Vd:
+        raise ValueError("shape mismatch between h, W_sub and d2t")
+    if tuple(out_target_ids.shape) != (rows, k) or tuple(out_logprobs.shape) != (rows, k) or \
+            out_logprobs.dtype != torch.float32 or not out_logprobs.is_contiguous():
+        raise ValueError("outputs must be contiguous [rows,k] int32 / float32 device tensors")
+    with torch.cuda.device(h.device):
+        st = lib().vt_draft_head_static(h.data_ptr(), rows, H, W_sub.data_ptr(), d2t.data_ptr(), Vd, k,
+                                        out_target_ids.data_ptr(), out_logprobs.data_ptr(), _stream_ptr(h))
+    if st != VT_OK:
+        raise VtError(st, "vt_draft_head_static")
     return out_target_ids, out_logprobs
 
 

@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "vt_internal.h"
 #include "vt_select.h"
 #include "vt_coverage.h"
@@ -40,6 +42,36 @@ static vt_status run_head(const uint16_t* h, int64_t rows, int64_t H, const uint
         return VT_ERR_DEVICE;
     if (!(p.regime == 0 && p.fused) && launch_merge(p, a, s) != hipSuccess)
         return VT_ERR_DEVICE;
+    return VT_OK;
+}
+
+// ---- device-resident scratch for callers that cannot allocate ----
+// One array per GPU (each device that loads the library holds its own copy at its own address,
+// until the process ends).  In host code the array's name is only a handle for the symbol
+// lookup; the device address obtained once per device is what every launch uses.  Its header
+// (the arrival counter) is zero at load time and every call leaves it zero.
+static __device__ __align__(256) unsigned char scratch[VT_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static std::atomic<char*> g_scratch_ptr[kMaxDevices];
+
+// Device address of the current device's scratch array; on the first use on a device also
+// enqueues a clear of its header on `s`.
+static vt_status static_scratch(hipStream_t s, char** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return VT_ERR_DEVICE;
+    char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+        void* addr = nullptr;
+        if (hipGetSymbolAddress(&addr, HIP_SYMBOL(scratch)) != hipSuccess || addr == nullptr)
+            return VT_ERR_DEVICE;
+        p = static_cast<char*>(addr);
+        if (launch_clear_words(reinterpret_cast<uint32_t*>(p), (int)(kWorkspaceHeader / sizeof(uint32_t)), s) != hipSuccess)
+            return VT_ERR_DEVICE;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
     return VT_OK;
 }
 
@@ -103,6 +135,25 @@ vt_status vt_draft_head_debug(const uint16_t* h, int64_t rows, int64_t H, const 
         return st;
     return run_head(h, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_logprobs, static_cast<char*>(workspace),
                     static_cast<hipStream_t>(stream), logits_out, lse_out);
+}
+
+vt_status vt_draft_head_static(const uint16_t* h, int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t,
+                               int64_t V_draft, int k, int32_t* out_target_ids, float* out_logprobs, void* stream)
+{
+    // the same argument checks, against the fixed capacity instead of a caller's buffer
+    const size_t need = vt_draft_head_workspace_bytes(rows, H, V_draft, k);
+    vt_status st = vt_validate_draft_head_args(h, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_logprobs,
+                                               reinterpret_cast<const void*>(uintptr_t{256}), need);
+    if (st != VT_OK)
+        return st;
+    if (need > (size_t)VT_STATIC_SCRATCH_BYTES)
+        return VT_ERR_WORKSPACE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    char* ws = nullptr;
+    st = static_scratch(s, &ws);
+    if (st != VT_OK)
+        return st;
+    return run_head(h, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_logprobs, ws, s, nullptr, nullptr);
 }
 
 vt_status vt_draft_head(const uint16_t* h, int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t,
