@@ -89,14 +89,17 @@ vt_status vt_validate_draft_head_args(const void *h, int64_t rows, int64_t H, co
 size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k);
 
 /*
- * One-time preparation of a workspace buffer for vt_draft_head: zeroes its 256-byte header, which
- * holds the arrival counter of the single-launch merge of the one- and two-row steps (Section
- * 2.3's head is one kernel there; the last workgroup to finish merges the partial results).
- * Every call leaves the counter at zero again, so one initialisation serves any number of calls
- * of any shapes; initialise again only if something else has written to the buffer.  Enqueues
- * one small kernel on `stream` (safe to record into a graph); VT_ERR_NULL / VT_ERR_WORKSPACE
- * (fewer than 256 bytes) / VT_ERR_ALIGN / VT_ERR_DEVICE.
+ * One-time preparation of a workspace buffer for vt_draft_head: zeroes its header of
+ * VT_WORKSPACE_HEADER_BYTES bytes, which holds the arrival counters of the single-launch merge of
+ * the one- and two-row steps (Section 2.3's head is one kernel there; the last workgroup to
+ * finish merges the partial results).  Every call leaves the counters at zero again, so one
+ * initialisation serves any number of calls of any shapes; initialise again only if something
+ * else has written to the buffer.  Enqueues one small kernel on `stream` (safe to record into a
+ * graph); VT_ERR_NULL / VT_ERR_WORKSPACE (fewer than VT_WORKSPACE_HEADER_BYTES bytes) /
+ * VT_ERR_ALIGN / VT_ERR_DEVICE.  Every size vt_draft_head_workspace_bytes returns includes the
+ * header.
  */
+#define VT_WORKSPACE_HEADER_BYTES 8192
 vt_status vt_draft_head_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
 /* Which kernel family serves this shape: 0 = streaming row-split kernels (memory bound,

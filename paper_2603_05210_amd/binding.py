@@ -17,6 +17,7 @@ LIB_PATH = _PKG / "libvt.so"
 
 VT_OK = 0
 VT_MAX_K = 64
+VT_WORKSPACE_HEADER_BYTES = 8192
 STATUS_NAMES = {
     0: "VT_OK", 1: "VT_ERR_NULL", 2: "VT_ERR_SHAPE", 3: "VT_ERR_K", 4: "VT_ERR_ID_RANGE",
     5: "VT_ERR_ID_DUP", 6: "VT_ERR_WORKSPACE", 7: "VT_ERR_ALIGN", 8: "VT_ERR_DEVICE",
@@ -165,7 +166,7 @@ def vt_draft_head_workspace_init(workspace: torch.Tensor) -> torch.Tensor:
 
 def new_workspace(nbytes: int, device) -> torch.Tensor:
     """A device buffer of at least `nbytes` bytes, initialised for vt_draft_head."""
-    return vt_draft_head_workspace_init(torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device))
+    return vt_draft_head_workspace_init(torch.empty(max(int(nbytes), VT_WORKSPACE_HEADER_BYTES), dtype=torch.uint8, device=device))
 
 
 class Workspace:

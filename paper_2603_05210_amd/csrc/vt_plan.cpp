@@ -10,6 +10,8 @@
 
 namespace vt {
 
+static_assert(kWorkspaceHeader == VT_WORKSPACE_HEADER_BYTES, "header size is part of the C ABI");
+
 static int next_pow2(int x)
 {
     int p = 1;
@@ -73,7 +75,22 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         if (lds > (size_t)kGemvLdsLimit)
             streaming = false;
     }
-    if (streaming) {
+    const bool one_row = rows == 1 && p.KP <= 16 && (H == 512 || H == 1024 || H == 2048 || H == 4096) &&
+                         Vd <= (int64_t)kGemvTargetBlocks * kGemvWaves * 64;
+    if (one_row) {
+        // one wave per run of W_sub rows, 16 waves per workgroup, at most one workgroup per compute unit
+        p.regime = 0;
+        p.one_row = 1;
+        p.KP = 16;  // the one-row kernel always carries lists of 16
+        p.NR = 1;
+        p.J = 1;
+        p.rpb = 0;
+        int blocks = (int)((Vd + kGemvWaves - 1) / kGemvWaves);
+        p.blocks = blocks > kGemvTargetBlocks ? kGemvTargetBlocks : blocks;  // measured: 128 or 64 workgroups are slower at every size
+        p.P = p.blocks;
+        p.fused = 1;
+        p.ks = 1;
+    } else if (streaming) {
         p.regime = 0;
         p.blocks = (int)((Vd + p.rpb - 1) / p.rpb);
         p.P = p.blocks;

@@ -19,10 +19,12 @@ constexpr int kGemvTargetBlocks = 256;     // one workgroup per compute unit of 
 // dynamic LDS a streaming kernel may ask for: the 160 KiB of a compute unit less the few bytes of
 // static LDS the kernels declare themselves
 constexpr int kGemvLdsLimit = 160 * 1024 - 256;
-// The caller's workspace starts with a header of this many bytes: word 0 is the arrival counter
-// of the single-launch merge (zero between calls: vt_draft_head_workspace_init zeroes it once, the
-// last workgroup of every call puts it back to zero).
-constexpr size_t kWorkspaceHeader = 256;
+// The caller's workspace starts with a header of this many bytes: the arrival counters of the
+// single-launch merge, one per 256 bytes so that no two share a cache line (counter 0: the call;
+// counters 1..16: groups of 16 workgroups).  All zero between calls: vt_draft_head_workspace_init
+// zeroes them once, and whoever sees a counter full puts it back to zero.
+constexpr size_t kWorkspaceHeader = 8192;  // = VT_WORKSPACE_HEADER_BYTES of the C header
+constexpr int kArriveStrideWords = 64;
 constexpr int kMergeThreads = 256;
 
 struct Plan {
@@ -33,6 +35,7 @@ struct Plan {
     int NR;      // rows rounded up to a power of two
     int J;       // W_sub rows a wave reduces together
     int rpb;     // W_sub rows per workgroup
+    int one_row; // the dedicated one-row kernel (H = 512, 1024, 2048 or 4096, lists of at most 16)
     int fused;   // the streaming kernel's last workgroup also does the final merge
     int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
     int ks;      // its slices of the hidden dimension per 16-row group (narrow ranges: keeps 16 waves busy)

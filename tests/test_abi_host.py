@@ -108,10 +108,10 @@ def test_regime_and_workspace_query(rows, H, Vd, k, regime):
 def test_workspace_init_argument_validation():
     f = vt.lib().vt_draft_head_workspace_init
     assert f(None, 4096, None) == 1
-    assert f(FAKE, 255, None) == 6
-    assert f(FAKE + 4, 4096, None) == 7
+    assert f(FAKE, 8191, None) == 6
+    assert f(FAKE + 4, 1 << 20, None) == 7
     # every workspace size includes the header the call initialises
-    assert vt.vt_draft_head_workspace_bytes(1, 64, 8, 1) >= 256 + 256
+    assert vt.vt_draft_head_workspace_bytes(1, 64, 8, 1) >= 8192 + 256
 
 
 def test_select_vocab_argument_validation():
