@@ -167,21 +167,11 @@ void vto_topk_row(const float *z, int64_t Vd, int k, int32_t *idx_out)
     free(e);
 }
 
-/*
- * The whole per-step head: logits, softmax normaliser over V_d, k best, d2t remap.
- *   out_ids[R,k]   ids in the target vocabulary, best first
- *   out_logp[R,k]  log-softmax over V_d of those tokens
- * Optional (may be NULL): out_draft_idx[R,k] positions inside V_d, z_out[R,Vd], lse_out[R],
- * flops.  Returns 0, or -1 when k is outside [1,Vd].
- */
-int vto_draft_head(const uint16_t *h, int64_t R, int64_t H, const uint16_t *W_sub,
-                   const int32_t *d2t, int64_t Vd, int k, int32_t *out_ids, float *out_logp,
-                   int32_t *out_draft_idx, float *z_out, float *lse_out, int64_t *flops)
+/* Rows of logits -> outputs: softmax normaliser over V_d, k best, d2t remap (shared by the
+ * bf16 head and the head over dequantised weights; z is [R,Vd]). */
+static void emit_rows(const float *z, int64_t R, int64_t Vd, const int32_t *d2t, int k, int32_t *out_ids,
+                      float *out_logp, int32_t *out_draft_idx, float *lse_out)
 {
-    if (k < 1 || k > Vd)
-        return -1;
-    float *z = z_out ? z_out : (float *)malloc((size_t)R * (size_t)Vd * sizeof(float));
-    vto_logits(h, R, H, W_sub, Vd, z, flops);
 #pragma omp parallel for schedule(dynamic)
     for (int64_t r = 0; r < R; ++r) {
         const float *zr = z + r * Vd;
@@ -198,6 +188,60 @@ int vto_draft_head(const uint16_t *h, int64_t R, int64_t H, const uint16_t *W_su
             lse_out[r] = lse;
         free(best);
     }
+}
+
+/*
+ * The whole per-step head: logits, softmax normaliser over V_d, k best, d2t remap.
+ *   out_ids[R,k]   ids in the target vocabulary, best first
+ *   out_logp[R,k]  log-softmax over V_d of those tokens
+ * Optional (may be NULL): out_draft_idx[R,k] positions inside V_d, z_out[R,Vd], lse_out[R],
+ * flops.  Returns 0, or -1 when k is outside [1,Vd].
+ */
+int vto_draft_head(const uint16_t *h, int64_t R, int64_t H, const uint16_t *W_sub,
+                   const int32_t *d2t, int64_t Vd, int k, int32_t *out_ids, float *out_logp,
+                   int32_t *out_draft_idx, float *z_out, float *lse_out, int64_t *flops)
+{
+    if (k < 1 || k > Vd)
+        return -1;
+    float *z = z_out ? z_out : (float *)malloc((size_t)R * (size_t)Vd * sizeof(float));
+    vto_logits(h, R, H, W_sub, Vd, z, flops);
+    emit_rows(z, R, Vd, d2t, k, out_ids, out_logp, out_draft_idx, lse_out);
+    if (!z_out)
+        free(z);
+    return 0;
+}
+
+/*
+ * The same head over a weight matrix given in fp32 (a compressed W_sub after dequantisation:
+ * the stored code times its scale, rounded once to fp32): bf16 hidden states, fp32 weights,
+ * sequential fp32 accumulation in ascending i with a separate multiply and add.
+ */
+void vto_logits_w32(const uint16_t *h, int64_t R, int64_t H, const float *W32, int64_t Vd, float *z)
+{
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t r = 0; r < R; ++r) {
+        for (int64_t j = 0; j < Vd; ++j) {
+            const uint16_t *hr = h + r * H;
+            const float *wj = W32 + j * H;
+            float acc = 0.0f;
+            for (int64_t i = 0; i < H; ++i) {
+                float prod = widen_bf16(hr[i]) * wj[i];
+                acc = acc + prod;
+            }
+            z[r * Vd + j] = acc;
+        }
+    }
+}
+
+int vto_draft_head_w32(const uint16_t *h, int64_t R, int64_t H, const float *W32, const int32_t *d2t,
+                       int64_t Vd, int k, int32_t *out_ids, float *out_logp, int32_t *out_draft_idx,
+                       float *z_out, float *lse_out)
+{
+    if (k < 1 || k > Vd)
+        return -1;
+    float *z = z_out ? z_out : (float *)malloc((size_t)R * (size_t)Vd * sizeof(float));
+    vto_logits_w32(h, R, H, W32, Vd, z);
+    emit_rows(z, R, Vd, d2t, k, out_ids, out_logp, out_draft_idx, lse_out);
     if (!z_out)
         free(z);
     return 0;

@@ -50,6 +50,10 @@ def _load():
         lib.vto_topk_row.argtypes = [p, i64, ctypes.c_int, p]
         lib.vto_draft_head.restype = ctypes.c_int
         lib.vto_draft_head.argtypes = [p, i64, i64, p, p, i64, ctypes.c_int, p, p, p, p, p, p]
+        lib.vto_logits_w32.restype = None
+        lib.vto_logits_w32.argtypes = [p, i64, i64, p, i64, p]
+        lib.vto_draft_head_w32.restype = ctypes.c_int
+        lib.vto_draft_head_w32.argtypes = [p, i64, i64, p, p, i64, ctypes.c_int, p, p, p, p, p]
         _lib = lib
     return _lib
 
@@ -146,4 +150,38 @@ def draft_head(h: np.ndarray, W_sub: np.ndarray, d2t: np.ndarray, k: int, want_l
     if rc != 0:
         raise ValueError("k must be in [1, V_draft]")
     res.flops = int(flops.value)
+    return res
+
+
+def logits_w32(h: np.ndarray, W32: np.ndarray) -> np.ndarray:
+    """z[R,Vd] fp32 for bf16 hidden states and fp32 weights (sequential fp32 accumulation)."""
+    h = _u16(h)
+    W32 = np.ascontiguousarray(W32, dtype=np.float32)
+    R, H = h.shape
+    Vd, H2 = W32.shape
+    assert H == H2
+    z = np.empty((R, Vd), dtype=np.float32)
+    _load().vto_logits_w32(_ptr(h), R, H, _ptr(W32), Vd, _ptr(z))
+    return z
+
+
+def draft_head_w32(h: np.ndarray, W32: np.ndarray, d2t: np.ndarray, k: int, want_logits: bool = True) -> HeadResult:
+    """The per-step head over fp32 weights (a dequantised compressed W_sub)."""
+    h = _u16(h)
+    W32 = np.ascontiguousarray(W32, dtype=np.float32)
+    d2t = np.ascontiguousarray(d2t, dtype=np.int32)
+    R, H = h.shape
+    Vd = W32.shape[0]
+    assert W32.shape[1] == H and d2t.shape[0] == Vd
+    res = HeadResult()
+    res.ids = np.empty((R, k), dtype=np.int32)
+    res.logp = np.empty((R, k), dtype=np.float32)
+    res.draft_idx = np.empty((R, k), dtype=np.int32)
+    res.z = np.empty((R, Vd), dtype=np.float32) if want_logits else None
+    res.lse = np.empty(R, dtype=np.float32)
+    rc = _load().vto_draft_head_w32(_ptr(h), R, H, _ptr(W32), _ptr(d2t), Vd, int(k), _ptr(res.ids),
+                                    _ptr(res.logp), _ptr(res.draft_idx), _ptr(res.z), _ptr(res.lse))
+    if rc != 0:
+        raise ValueError("k must be in [1, V_draft]")
+    res.flops = 2 * R * H * Vd
     return res
