@@ -158,6 +158,50 @@ vt_status vt_draft_head_debug(const uint16_t *h, int64_t rows, int64_t H, const 
                               float *logits_out, float *lse_out);
 
 /*
+ * Compressed W_sub for the one-row draft step.  Sections 1 and 2.3: the head dominates the
+ * draft's latency and costs 2*d*k per token; at one row that is the bytes of W_sub, which
+ * trimming cuts through k and a narrower storage format cuts per weight.  Two formats:
+ *   VT_Q_FP8_E4M3  one byte per weight: OCP E4M3 (bias 7, no infinities, largest value 448),
+ *                  one fp32 scale per row: scale_j = max_i |W[j,i]| / 448 (1 for an all-zero row),
+ *                  code = E4M3(W[j,i] / scale_j), nearest, ties to even, saturating.  H % 16 == 0.
+ *   VT_Q_MXFP4     OCP microscaling: E2M1 codes (0, 0.5, 1, 1.5, 2, 3, 4, 6 and their negatives),
+ *                  two per byte with the even element in the low nibble, and one exponent byte
+ *                  (power of two, bias 127) per 32 consecutive weights of a row:
+ *                  exponent = floor(log2(max |w| of the block)) - 2 (byte 127 for an all-zero
+ *                  block), code = E2M1(w / 2^exponent).  H % 32 == 0.
+ * vt_build_subset_q is vt_build_subset with the gathered rows stored in one of these formats:
+ *   codes_out   device, vt_subset_q_code_bytes(...) bytes: [V_draft][H] (FP8) or [V_draft][H/2] (MXFP4)
+ *   scales_out  device, vt_subset_q_scale_bytes(...) bytes: float[V_draft] (FP8) or
+ *               uint8[V_draft][H/32] (MXFP4); both 16-byte aligned
+ * Same id checks, waiting and error codes as vt_build_subset; VT_ERR_SHAPE for an unknown format.
+ */
+#define VT_Q_FP8_E4M3 1
+#define VT_Q_MXFP4 2
+size_t vt_subset_q_code_bytes(int fmt, int64_t V_draft, int64_t H);   /* 0 on invalid arguments */
+size_t vt_subset_q_scale_bytes(int fmt, int64_t V_draft, int64_t H);
+vt_status vt_build_subset_q(const uint16_t *full_W, int64_t V, int64_t H, const int32_t *token_ids,
+                            int64_t V_draft, int fmt, uint8_t *codes_out, void *scales_out, int32_t *d2t_out,
+                            void *stream);
+
+/*
+ * One draft step over a compressed W_sub: vt_draft_head's computation with every weight taken
+ * as its code's value times its scale (bf16 hidden state, exact products, fp32 accumulation; the
+ * scale multiplies the fp32 sum of its row or 32-weight block).  Served shapes: rows == 1 (the
+ * memory-bound regime the compression is for), k <= 16, V_draft <= 262144, H in {1024, 2048,
+ * 4096} (FP8) or {2048, 4096} (MXFP4); anything else is VT_ERR_SHAPE (VT_ERR_K for k).  Pointers,
+ * workspace rules (vt_draft_head_workspace_init once), asynchrony and outputs as vt_draft_head;
+ * the _debug form also stores logits_out[V_draft] and lse_out[1] (either may be NULL).
+ */
+size_t vt_draft_head_q_workspace_bytes(int fmt, int64_t rows, int64_t H, int64_t V_draft, int k);
+vt_status vt_draft_head_q(const uint16_t *h, int64_t rows, int64_t H, const uint8_t *codes, const void *scales,
+                          int fmt, const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
+                          float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream);
+vt_status vt_draft_head_q_debug(const uint16_t *h, int64_t rows, int64_t H, const uint8_t *codes, const void *scales,
+                                int fmt, const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
+                                float *out_logprobs, void *workspace, size_t workspace_bytes, void *stream,
+                                float *logits_out, float *lse_out);
+
+/*
  * Draft-vocabulary size selection (Section 2, Eq. 1-5).  From a stream of token ids (the
  * assistant-span tokens of a training corpus, Section 2.2) the call computes, on the device:
  *   f(v)   the frequency of every token id (freq_out),

@@ -28,7 +28,8 @@ EXPORTS = (
     "vt_version", "vt_status_str", "vt_build_subset", "vt_check_token_ids_host",
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
     "vt_draft_head_workspace_init", "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug",
-    "vt_draft_head_static",
+    "vt_draft_head_static", "vt_subset_q_code_bytes", "vt_subset_q_scale_bytes", "vt_build_subset_q",
+    "vt_draft_head_q_workspace_bytes", "vt_draft_head_q", "vt_draft_head_q_debug",
     "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
     "vt_select_vocab", "vt_build_t2d", "vt_coverage_workspace_bytes", "vt_coverage",
 )
@@ -71,6 +72,18 @@ def lib() -> ctypes.CDLL:
         L.vt_draft_head.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p]
         L.vt_draft_head_static.restype = i32
         L.vt_draft_head_static.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p]
+        L.vt_subset_q_code_bytes.restype = sz
+        L.vt_subset_q_code_bytes.argtypes = [i32, i64, i64]
+        L.vt_subset_q_scale_bytes.restype = sz
+        L.vt_subset_q_scale_bytes.argtypes = [i32, i64, i64]
+        L.vt_build_subset_q.restype = i32
+        L.vt_build_subset_q.argtypes = [p, i64, i64, p, i64, i32, p, p, p, p]
+        L.vt_draft_head_q_workspace_bytes.restype = sz
+        L.vt_draft_head_q_workspace_bytes.argtypes = [i32, i64, i64, i64, i32]
+        L.vt_draft_head_q.restype = i32
+        L.vt_draft_head_q.argtypes = [p, i64, i64, p, p, i32, p, i64, i32, p, p, p, sz, p]
+        L.vt_draft_head_q_debug.restype = i32
+        L.vt_draft_head_q_debug.argtypes = [p, i64, i64, p, p, i32, p, i64, i32, p, p, p, sz, p, p, p]
         L.vt_draft_head_debug.restype = i32
         L.vt_draft_head_debug.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p]
         L.vt_draft_head_workspace_init.restype = i32
@@ -245,6 +258,68 @@ def vt_draft_head_static(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor
                                         out_target_ids.data_ptr(), out_logprobs.data_ptr(), _stream_ptr(h))
     if st != VT_OK:
         raise VtError(st, "vt_draft_head_static")
+    return out_target_ids, out_logprobs
+
+
+VT_Q_FP8_E4M3 = 1
+VT_Q_MXFP4 = 2
+
+
+def vt_build_subset_q(full_W: torch.Tensor, token_ids: torch.Tensor, fmt: int):
+    """Compressed W_sub for the draft vocabulary `token_ids`: (codes uint8, scales, d2t) device tensors.
+    FP8: codes [V_draft,H], scales float32 [V_draft]; MXFP4: codes [V_draft,H/2], scales uint8 [V_draft,H/32]."""
+    _dev16(full_W, "full_W")
+    _devi32(token_ids, "token_ids")
+    V, H = full_W.shape
+    Vd = token_ids.shape[0]
+    L = lib()
+    nc, ns = int(L.vt_subset_q_code_bytes(fmt, Vd, H)), int(L.vt_subset_q_scale_bytes(fmt, Vd, H))
+    if nc == 0:
+        raise VtError(2, "vt_build_subset_q")
+    dev = full_W.device
+    codes = torch.empty((Vd, nc // Vd), dtype=torch.uint8, device=dev)
+    scales = (torch.empty((Vd,), dtype=torch.float32, device=dev) if fmt == VT_Q_FP8_E4M3
+              else torch.empty((Vd, ns // Vd), dtype=torch.uint8, device=dev))
+    d2t = torch.empty((Vd,), dtype=torch.int32, device=dev)
+    with torch.cuda.device(dev):
+        st = L.vt_build_subset_q(full_W.data_ptr(), V, H, token_ids.data_ptr(), Vd, fmt, codes.data_ptr(),
+                                 scales.data_ptr(), d2t.data_ptr(), _stream_ptr(full_W))
+    if st != VT_OK:
+        raise VtError(st, "vt_build_subset_q")
+    return codes, scales, d2t
+
+
+def vt_draft_head_q_workspace_bytes(fmt: int, rows: int, H: int, V_draft: int, k: int) -> int:
+    return int(lib().vt_draft_head_q_workspace_bytes(fmt, rows, H, V_draft, k))
+
+
+def vt_draft_head_q(h: torch.Tensor, codes: torch.Tensor, scales: torch.Tensor, fmt: int, d2t: torch.Tensor, k: int,
+                    out_target_ids: torch.Tensor | None = None, out_logprobs: torch.Tensor | None = None,
+                    workspace: torch.Tensor | None = None, logits_out: torch.Tensor | None = None,
+                    lse_out: torch.Tensor | None = None):
+    """One draft step over a compressed W_sub (one row): (target ids [1,k], log-probs [1,k])."""
+    _dev16(h, "h")
+    _devi32(d2t, "d2t")
+    if not (codes.is_cuda and codes.is_contiguous() and codes.dtype == torch.uint8 and scales.is_cuda
+            and scales.is_contiguous()):
+        raise TypeError("codes / scales must be contiguous device tensors")
+    rows, H = h.shape
+    Vd = codes.shape[0]
+    dev = h.device
+    if out_target_ids is None:
+        out_target_ids = torch.empty((rows, k), dtype=torch.int32, device=dev)
+    if out_logprobs is None:
+        out_logprobs = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(vt_draft_head_q_workspace_bytes(fmt, rows, H, Vd, k), dev)
+    with torch.cuda.device(dev):
+        st = lib().vt_draft_head_q_debug(h.data_ptr(), rows, H, codes.data_ptr(), scales.data_ptr(), fmt, d2t.data_ptr(),
+                                         Vd, k, out_target_ids.data_ptr(), out_logprobs.data_ptr(),
+                                         workspace.data_ptr(), workspace.numel(), _stream_ptr(h),
+                                         None if logits_out is None else logits_out.data_ptr(),
+                                         None if lse_out is None else lse_out.data_ptr())
+    if st != VT_OK:
+        raise VtError(st, "vt_draft_head_q")
     return out_target_ids, out_logprobs
 
 

@@ -9,6 +9,7 @@
 #include <atomic>
 
 #include "vt_internal.h"
+#include "vt_gemv_common.h"
 #include "vt_select.h"
 #include "vt_coverage.h"
 
@@ -20,14 +21,15 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 // has been initialised (arrival counter zero).
 static vt_status run_head(const uint16_t* h, int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t,
                           int64_t V_draft, int k, int32_t* out_target_ids, float* out_logprobs, char* ws,
-                          hipStream_t s, float* logits_out, float* lse_out)
+                          hipStream_t s, float* logits_out, float* lse_out, int fmt = 0, const void* scales = nullptr)
 {
     Plan p;
-    if (!make_plan(rows, H, V_draft, k, p))
+    if (!(fmt == 0 ? make_plan(rows, H, V_draft, k, p) : make_plan_q(fmt, rows, H, V_draft, k, p)))
         return VT_ERR_SHAPE;
     HeadArgs a;
     a.h = h;
     a.W = W_sub;
+    a.scales = scales;
     a.d2t = d2t;
     a.out_ids = out_target_ids;
     a.out_logp = out_logprobs;
@@ -37,11 +39,34 @@ static vt_status run_head(const uint16_t* h, int64_t rows, int64_t H, const uint
     a.part_stat = reinterpret_cast<float2*>(ws + p.off_stat);
     a.logits_out = logits_out;
     a.lse_out = lse_out;
-    const hipError_t e = (p.regime == 0) ? launch_gemv(p, a, s) : launch_gemm(p, a, s);
+    const hipError_t e = fmt != 0 ? launch_gemv_q(fmt, p, a, s) : (p.regime == 0) ? launch_gemv(p, a, s) : launch_gemm(p, a, s);
     if (e != hipSuccess)
         return VT_ERR_DEVICE;
     if (!(p.regime == 0 && p.fused) && launch_merge(p, a, s) != hipSuccess)
         return VT_ERR_DEVICE;
+    return VT_OK;
+}
+
+// Range and distinctness of a draft vocabulary's ids, checked on the device; waits for the
+// answer.  Allocates and frees a V-bit bitmap (set-up path).
+static vt_status check_ids_on_device(const int32_t* token_ids, int64_t V_draft, int64_t V, hipStream_t s)
+{
+    const size_t words = (size_t)(V + 31) / 32;
+    uint32_t* bits = nullptr;  // bitmap words, then one int of error bits
+    if (hipMalloc(reinterpret_cast<void**>(&bits), (words + 1) * sizeof(uint32_t)) != hipSuccess)
+        return VT_ERR_DEVICE;
+    int err = 0;
+    bool ok = hipMemsetAsync(bits, 0, (words + 1) * sizeof(uint32_t), s) == hipSuccess;
+    ok = ok && launch_check_ids(token_ids, (int)V_draft, (int)V, bits, reinterpret_cast<int*>(bits + words), s) == hipSuccess;
+    ok = ok && hipMemcpyAsync(&err, bits + words, sizeof(int), hipMemcpyDeviceToHost, s) == hipSuccess;
+    ok = ok && hipStreamSynchronize(s) == hipSuccess;
+    (void)hipFree(bits);
+    if (!ok)
+        return VT_ERR_DEVICE;
+    if (err & 1)
+        return VT_ERR_ID_RANGE;
+    if (err & 2)
+        return VT_ERR_ID_DUP;
     return VT_OK;
 }
 
@@ -88,24 +113,32 @@ vt_status vt_build_subset(const uint16_t* full_W, int64_t V, int64_t H, const in
     if (st != VT_OK)
         return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t words = (size_t)(V + 31) / 32;
-    uint32_t* scratch = nullptr;  // bitmap words, then one int of error bits
-    if (hipMalloc(reinterpret_cast<void**>(&scratch), (words + 1) * sizeof(uint32_t)) != hipSuccess)
-        return VT_ERR_DEVICE;
-    int err = 0;
-    bool ok = hipMemsetAsync(scratch, 0, (words + 1) * sizeof(uint32_t), s) == hipSuccess;
-    ok = ok && launch_check_ids(token_ids, (int)V_draft, (int)V, scratch, reinterpret_cast<int*>(scratch + words), s) ==
-                   hipSuccess;
-    ok = ok && hipMemcpyAsync(&err, scratch + words, sizeof(int), hipMemcpyDeviceToHost, s) == hipSuccess;
-    ok = ok && hipStreamSynchronize(s) == hipSuccess;
-    (void)hipFree(scratch);
-    if (!ok)
-        return VT_ERR_DEVICE;
-    if (err & 1)
-        return VT_ERR_ID_RANGE;
-    if (err & 2)
-        return VT_ERR_ID_DUP;
+    st = check_ids_on_device(token_ids, V_draft, V, s);
+    if (st != VT_OK)
+        return st;
     if (launch_gather(full_W, (int)H, token_ids, (int)V_draft, W_sub_out, d2t_out, s) != hipSuccess)
+        return VT_ERR_DEVICE;
+    return VT_OK;
+}
+
+vt_status vt_build_subset_q(const uint16_t* full_W, int64_t V, int64_t H, const int32_t* token_ids, int64_t V_draft,
+                            int fmt, uint8_t* codes_out, void* scales_out, int32_t* d2t_out, void* stream)
+{
+    if (!codes_out || !scales_out)
+        return VT_ERR_NULL;
+    // the bf16 call's checks (pointers, ranges, alignment) with the code buffer in W_sub's place
+    vt_status st = vt_validate_build_subset_args(full_W, V, H, token_ids, V_draft, codes_out, d2t_out);
+    if (st != VT_OK)
+        return st;
+    if (vt_subset_q_code_bytes(fmt, V_draft, H) == 0)
+        return VT_ERR_SHAPE;
+    if (!aligned16(scales_out))
+        return VT_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = check_ids_on_device(token_ids, V_draft, V, s);
+    if (st != VT_OK)
+        return st;
+    if (launch_quant_gather(fmt, full_W, (int)H, token_ids, (int)V_draft, codes_out, scales_out, d2t_out, s) != hipSuccess)
         return VT_ERR_DEVICE;
     return VT_OK;
 }
@@ -135,6 +168,36 @@ vt_status vt_draft_head_debug(const uint16_t* h, int64_t rows, int64_t H, const 
         return st;
     return run_head(h, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_logprobs, static_cast<char*>(workspace),
                     static_cast<hipStream_t>(stream), logits_out, lse_out);
+}
+
+vt_status vt_draft_head_q_debug(const uint16_t* h, int64_t rows, int64_t H, const uint8_t* codes, const void* scales,
+                                int fmt, const int32_t* d2t, int64_t V_draft, int k, int32_t* out_target_ids,
+                                float* out_logprobs, void* workspace, size_t workspace_bytes, void* stream,
+                                float* logits_out, float* lse_out)
+{
+    if (!h || !codes || !scales || !d2t || !out_target_ids || !out_logprobs)
+        return VT_ERR_NULL;
+    if (k < 1 || k > 16 || k > V_draft)
+        return VT_ERR_K;
+    const size_t need = vt_draft_head_q_workspace_bytes(fmt, rows, H, V_draft, k);
+    if (need == 0)
+        return VT_ERR_SHAPE;
+    if (!workspace || workspace_bytes < need)
+        return VT_ERR_WORKSPACE;
+    if (!aligned16(h) || !aligned16(codes) || !aligned16(scales) || !aligned16(workspace) ||
+        (reinterpret_cast<uintptr_t>(d2t) & 3u) || (reinterpret_cast<uintptr_t>(out_target_ids) & 3u) ||
+        (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
+        return VT_ERR_ALIGN;
+    return run_head(h, rows, H, reinterpret_cast<const uint16_t*>(codes), d2t, V_draft, k, out_target_ids, out_logprobs,
+                    static_cast<char*>(workspace), static_cast<hipStream_t>(stream), logits_out, lse_out, fmt, scales);
+}
+
+vt_status vt_draft_head_q(const uint16_t* h, int64_t rows, int64_t H, const uint8_t* codes, const void* scales, int fmt,
+                          const int32_t* d2t, int64_t V_draft, int k, int32_t* out_target_ids, float* out_logprobs,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    return vt_draft_head_q_debug(h, rows, H, codes, scales, fmt, d2t, V_draft, k, out_target_ids, out_logprobs, workspace,
+                                 workspace_bytes, stream, nullptr, nullptr);
 }
 
 vt_status vt_draft_head_static(const uint16_t* h, int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t,

@@ -466,11 +466,40 @@ static hipError_t launch_one(const Plan& p, const GemvArgs& ga, hipStream_t s)
     return hipGetLastError();
 }
 
+static void fill_gemv_args(const Plan& p, const HeadArgs& a, GemvArgs& ga);
+
+hipError_t launch_gemv_q(int fmt, const Plan& p, const HeadArgs& a, hipStream_t s)
+{
+    GemvArgs ga;
+    fill_gemv_args(p, a, ga);
+    ga.nchunk = 0;  // the compressed kernels take the row length from the plan's hidden size
+    return launch_gemv_one_row_q(fmt, p, ga, s);
+}
+
 hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
 {
     GemvArgs ga;
+    fill_gemv_args(p, a, ga);
+    if (p.one_row)
+        return launch_gemv_one_row(p, ga, s);
+    if (p.mfma)
+        return launch_mfma(p, ga, s);
+    // rows of W_sub a wave reduces together (J): measured best 1 for a single hidden row, 2 otherwise
+    switch (p.NR) {
+    case 1: return launch_one<1, 1, true>(p, ga, s);
+    case 2: return launch_one<2, 2, true>(p, ga, s);
+    case 4: return launch_one<4, 2, true>(p, ga, s);
+    case 8: return launch_one<8, 2, true>(p, ga, s);
+    case 16: return launch_one<16, 2, true>(p, ga, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+static void fill_gemv_args(const Plan& p, const HeadArgs& a, GemvArgs& ga)
+{
     ga.h = reinterpret_cast<const u32x4*>(a.h);
     ga.W = reinterpret_cast<const u32x4*>(a.W);
+    ga.scales = a.scales;
     ga.rows = p.rows;
     ga.nchunk = p.H / 8;
     ga.Vd = p.Vd;
@@ -489,19 +518,6 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     ga.out_ids = a.out_ids;
     ga.out_logp = a.out_logp;
     ga.lse_out = a.lse_out;
-    if (p.one_row)
-        return launch_gemv_one_row(p, ga, s);
-    if (p.mfma)
-        return launch_mfma(p, ga, s);
-    // rows of W_sub a wave reduces together (J): measured best 1 for a single hidden row, 2 otherwise
-    switch (p.NR) {
-    case 1: return launch_one<1, 1, true>(p, ga, s);
-    case 2: return launch_one<2, 2, true>(p, ga, s);
-    case 4: return launch_one<4, 2, true>(p, ga, s);
-    case 8: return launch_one<8, 2, true>(p, ga, s);
-    case 16: return launch_one<16, 2, true>(p, ga, s);
-    }
-    return hipErrorInvalidValue;
 }
 
 }  // namespace vt

@@ -1,403 +1,17 @@
-// The one-row draft step (the paper's own operating point: one hidden state per draft token,
-// Section 2.3's projection over a few thousand to 128 K draft tokens).  The step is bound by
-// reading W_sub once, and at the vocabulary sizes the paper selects (Sections 2.6, 3.2) the whole
-// read takes only a few microseconds, so everything around the stream is latency:
-//
-//   - a workgroup owns a contiguous run of W_sub rows and hands them out to its 16 waves in
-//     order from an LDS counter (a wave that is served faster by memory takes more rows); a wave
-//     keeps 8 KiB of loads in flight and turns each 1 KiB piece over as soon as it has arrived;
-//   - the hidden state never goes through LDS: lane l always multiplies column pieces l, l+64,
-//     ... of a row, so it keeps exactly those pieces of h in registers (no staging before the
-//     stream starts);
-//   - a row's logit comes out of a DPP / permlane butterfly wave-uniform and is inserted there
-//     and then into the wave's running list of the 16 best (lane q of every 16-lane row holds
-//     the q-th best; one shifted copy and two compares per row), under the latency of the loads
-//     in flight; the logit also goes to its place in LDS so that the softmax statistics are
-//     summed in a fixed order whatever wave happened to take the row;
-//   - lists are merged by a bitonic network on 64-bit order keys (logit key, then lower draft
-//     index) held one list per 16-lane row: no rounds, no data-dependent control flow, the same
-//     primitive for the workgroup's 16 wave lists and for the final merge of all workgroups'
-//     lists by the last workgroup to arrive (single launch per step).
-#include <atomic>
-#include <type_traits>
-
-#include "vt_gemv_common.h"
+// The one-row draft step over a bf16 W_sub: instantiations of the generic one-row kernel.
+#include "vt_onerow.h"
 
 namespace vt {
 
-constexpr int kKeyMax = 0x7fffffff;
-
-// Value of lane l-1 of the same 16-lane row; lane 0 of a row gets `fill`.
-__device__ __forceinline__ int row_shr1(int x, int fill)
-{
-    return __builtin_amdgcn_update_dpp(fill, x, 0x111, 0xf, 0xf, false);
-}
-
-// ---- 64-bit order keys: a candidate (logit, draft index) as one integer, larger = better ----
-// high word: the order-preserving key of the logit; low word: 0x7fffffff - index, so that of
-// two equal logits the lower index is the larger key.  Distinct candidates have distinct keys
-// (the empty marker, key of -inf with index kIdxNone, is the smallest of all and may repeat).
-typedef long long k64;
-__device__ __forceinline__ k64 k64_make(int key, int idx)
-{
-    return (k64)(((unsigned long long)(unsigned int)key << 32) | (unsigned int)(kIdxNone - idx));
-}
-__device__ __forceinline__ int k64_key(k64 x) { return (int)(x >> 32); }
-__device__ __forceinline__ int k64_idx(k64 x) { return kIdxNone - (int)(unsigned int)x; }
-
-__device__ __forceinline__ k64 k64_row_mirror(k64 x)  // lane q of a 16-lane row <- lane 15-q
-{
-    const int lo = __builtin_amdgcn_mov_dpp((int)(unsigned int)x, 0x140, 0xf, 0xf, true);
-    const int hi = __builtin_amdgcn_mov_dpp((int)(x >> 32), 0x140, 0xf, 0xf, true);
-    return (k64)(((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo);
-}
-template <int OFF>
-__device__ __forceinline__ k64 k64_xchg(k64 x, int lane)  // value of lane l ^ OFF
-{
-    const int lo = xchg_i<OFF>((int)(unsigned int)x, lane);
-    const int hi = xchg_i<OFF>((int)(x >> 32), lane);
-    return (k64)(((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo);
-}
-// One stage of the bitonic sorter inside a 16-lane row: the lower lane of a pair keeps the
-// larger key.
-template <int OFF>
-__device__ __forceinline__ k64 k64_stage(k64 c, int lane)
-{
-    const k64 p = k64_xchg<OFF>(c, lane);
-    const bool lower = (lane & OFF) == 0;
-    return ((p > c) == lower) ? p : c;
-}
-// a, b: lists of 16 keys sorted best first, one per 16-lane row (lane q holds the q-th).
-// Returns the 16 best of their union, sorted best first: max(a, reversed b) is a bitonic
-// sequence holding exactly those 16, which four compare-exchange stages sort.
-__device__ __forceinline__ k64 k64_merge16(k64 a, k64 b, int lane)
-{
-    const k64 br = k64_row_mirror(b);
-    k64 c = a > br ? a : br;
-    c = k64_stage<8>(c, lane);
-    c = k64_stage<4>(c, lane);
-    c = k64_stage<2>(c, lane);
-    c = k64_stage<1>(c, lane);
-    return c;
-}
-// 16 sorted lists of 16 keys, stored back to back at `lists` (LDS), merged by one wave: every
-// 16-lane row returns the 16 best of all 256, sorted best first.
-__device__ __forceinline__ k64 k64_merge_16_lists(const k64* lists, int lane)
-{
-    const k64 s0 = lists[lane], s1 = lists[64 + lane], s2 = lists[128 + lane], s3 = lists[192 + lane];
-    const k64 m01 = k64_merge16(s0, s1, lane);
-    const k64 m23 = k64_merge16(s2, s3, lane);
-    k64 m = k64_merge16(m01, m23, lane);          // row r now holds the best of lists r, 4+r, 8+r, 12+r
-    m = k64_merge16(m, k64_xchg<16>(m, lane), lane);  // rows 0|1 and 2|3
-    m = k64_merge16(m, k64_xchg<32>(m, lane), lane);  // all four rows
-    return m;
-}
-
-// Device-coherent loads of what other workgroups published, issued back to back and awaited
-// once (the compiler's own atomic loads wait for each load separately).  The wait takes the
-// destinations as operands, so no use can be scheduled ahead of it.
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ void coherent_load_issue(f32x4& dst, const float* p)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
-}
-__device__ __forceinline__ void coherent_load_issue(i32x4& dst, const int* p)
-{
-    asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
-}
-__device__ __forceinline__ void coherent_load_issue(float2& dst, const float2* p)
-{
-    asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
-}
-__device__ __forceinline__ void coherent_load_wait(f32x4& a, i32x4& b, float2& c)
-{
-    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
-}
-
-constexpr int kOneRowMaxRowsPerBlock = 1024;  // W_sub rows a workgroup may own (LDS place per logit)
-
-// LDS map of the kernel (bytes)
-constexpr int kLdsZ = 0;                                        // float[1024]  logits of the workgroup's rows
-constexpr int kLdsWl = kLdsZ + kOneRowMaxRowsPerBlock * 4;      // k64[16][16]  wave lists
-constexpr int kLdsWst = kLdsWl + 16 * 16 * 8;                   // float2[16]   slice statistics
-constexpr int kLdsCand = kLdsWst + 16 * 8;                      // k64[256][16] all workgroups' lists (final merge)
-constexpr int kLdsWl2 = kLdsCand + 256 * 16 * 8;                // k64[16][16]  per-wave results of the final merge
-constexpr int kLdsFst = kLdsWl2 + 16 * 16 * 8;                  // float2[16]
-constexpr int kLdsTotal = kLdsFst + 16 * 8;
-constexpr int kLdsH = kLdsCand;  // u32x4[512]: the hidden state on its way to the waves' registers (dead before the final merge)
-
-// T: KiB per W_sub row (H = 512 * T); 8 KiB in flight per wave.
-template <int T>
-__global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
-{
-    constexpr int D = 8;
-    constexpr int G = D / T;  // W_sub rows per hand-out (one loop iteration)
-    static_assert(D % T == 0, "a loop iteration covers whole rows");
-    extern __shared__ u32x4 smem[];
-    __shared__ int s_last;
-    __shared__ unsigned int s_next;
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    constexpr int nchunk = T * 64;
-    char* lds = reinterpret_cast<char*>(smem);
-    float* zbuf = reinterpret_cast<float*>(lds + kLdsZ);
-    k64* wl = reinterpret_cast<k64*>(lds + kLdsWl);
-    float2* wst = reinterpret_cast<float2*>(lds + kLdsWst);
-
-    // rows of this workgroup: an even split of V_draft over the grid, in order
-    const int nb = gridDim.x;
-    const int b = blockIdx.x;
-    const int base = a.Vd / nb;
-    const int rem = a.Vd - base * nb;
-    const int n_wg = base + (b < rem ? 1 : 0);
-    const int j0 = b * base + (b < rem ? b : rem);
-    const int ngroups = (n_wg + G - 1) / G;
-    const int nfull = n_wg / G;  // groups below this index have all G rows
-
-    const u32x4* wp = a.W + (size_t)j0 * nchunk + lane;
-    auto slot_ptr = [&](int grp, int i) { return wp + (size_t)(grp * G + i / T) * nchunk + (i % T) * kWave; };
-
-    // the hidden state: one 8-byte piece per thread, requested before anything else
-    const int hpiece = tid < nchunk * 2 ? tid : nchunk * 2 - 1;
-    const uint2 hval = reinterpret_cast<const uint2*>(a.h)[hpiece];
-    __builtin_amdgcn_sched_barrier(0);
-    // the first hand-out is the wave's own number; later ones come from the counter
-    if (tid == 0)
-        s_next = kGemvWaves;
-    int gc = wave;
-    u32x4 buf[D];
-    // The first pieces of W_sub are requested, then h goes through LDS to every wave.  When the
-    // wave's first hand-out is full its loads are unconditional, so the compiler knows how many
-    // loads follow the h piece and waits for that piece alone (loads return in order).  The
-    // counter is set before any wave draws from it.  A bare barrier behind the LDS writes: a full
-    // __syncthreads would drain the W_sub loads in flight.
-    u32x4 hreg[T];
-    auto stage_h = [&]() {
-        reinterpret_cast<uint2*>(lds + kLdsH)[hpiece] = hval;
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
-        __builtin_amdgcn_s_barrier();        // every wave passes exactly one of the two barriers below
-#pragma unroll
-        for (int t = 0; t < T; ++t)
-            hreg[t] = reinterpret_cast<const u32x4*>(lds + kLdsH)[t * kWave + lane];
-    };
-    if (gc < nfull) {
-#pragma unroll
-        for (int i = 0; i < D; ++i)
-            buf[i] = __builtin_nontemporal_load(slot_ptr(gc, i));
-        stage_h();
-        asm volatile("; first hand-out full");  // keeps the two copies apart (exact load count in this one)
-    } else {
-#pragma unroll
-        for (int i = 0; i < D; ++i) {
-            if (gc * G + i / T < n_wg)
-                buf[i] = __builtin_nontemporal_load(slot_ptr(gc, i));
-        }
-        stage_h();
-        asm volatile("; first hand-out partial or none");
-    }
-    auto grab = [&]() {
-        unsigned int v = 0;
-        if (lane == 0)
-            v = atomicAdd(&s_next, 1u);
-        return v;
-    };
-    int gn = (int)__builtin_amdgcn_readfirstlane(grab());
-
-    int lkey = kKeyNone, lidx = kIdxNone;  // the wave's 16 best so far: lane q of each 16-lane row holds the q-th
-    float acc = 0.0f;
-    // One iteration = the D pieces (G whole rows) of hand-out gc; the pieces of hand-out gn are
-    // requested one by one as the current ones are consumed.  STEADY: both hand-outs are full,
-    // so every load and every row is unconditional and the compiler counts the loads in flight
-    // exactly; otherwise rows and loads are guarded.
-    auto iteration = [&](auto steady_c) {
-        constexpr bool STEADY = decltype(steady_c)::value;
-        const unsigned int gnn_raw = grab();  // the hand-out after next: its LDS round trip hides under this iteration
-#pragma unroll
-        for (int i = 0; i < D; ++i) {
-            const int rr = gc * G + i / T;  // row within the workgroup's run
-            if (STEADY || rr < n_wg) {
-                const u32x4 cur = buf[i];
-                if (STEADY || gn * G + i / T < n_wg)
-                    buf[i] = __builtin_nontemporal_load(slot_ptr(gn, i));
-                acc = dot8<true>(cur, hreg[i % T], acc);
-                if (i % T == T - 1) {
-                    float pv[1] = {acc};
-                    const float z = reduce_pairs<1>(pv, lane);
-                    acc = 0.0f;
-                    const int zk = f2key(z);
-                    const int j = j0 + rr;
-                    const int sk = row_shr1(lkey, kKeyMax);
-                    const int si = row_shr1(lidx, kIdxNone);
-                    const bool c0 = zk > lkey;  // a wave's rows ascend: ties keep the earlier (lower) index ahead
-                    const bool c1 = zk > sk;
-                    lkey = c0 ? (c1 ? sk : zk) : lkey;
-                    lidx = c0 ? (c1 ? si : j) : lidx;
-                    if (lane == 0) {
-                        zbuf[rr] = z;
-                        if (a.logits_out != nullptr)
-                            a.logits_out[j] = z;
-                    }
-                }
-            }
-            if (STEADY)
-                __builtin_amdgcn_sched_barrier(0);  // keep "consume piece i, request its successor" in this order
-        }
-        gc = gn;
-        gn = (int)__builtin_amdgcn_readfirstlane(gnn_raw);
-    };
-    while (gc < ngroups) {
-        if (gc < nfull && gn < nfull)
-            iteration(std::true_type{});
-        else
-            iteration(std::false_type{});
-    }
-
-    // ---- the wave's list goes to LDS ----
-    if (lane < 16)
-        wl[wave * 16 + lane] = k64_make(lkey, lidx);
-    __syncthreads();
-
-    // ---- wave 0 merges the 16 lists; waves 1..15 sum the softmax statistics over fixed slices ----
-    k64 best = 0;
-    if (wave == 0) {
-        best = k64_merge_16_lists(wl, lane);
-    } else {
-        const int per = (n_wg + 14) / 15;  // at most 69 logits per slice: two per lane
-        const int lo = (wave - 1) * per;
-        const int hi = lo + per < n_wg ? lo + per : n_wg;
-        const int e0 = lo + lane, e1 = lo + kWave + lane;
-        const float v0 = e0 < hi ? zbuf[e0] : neg_inf();
-        const float v1 = e1 < hi ? zbuf[e1] : neg_inf();
-        float m = neg_inf(), s = 0.0f;
-        if (lo < hi) {
-            m = wave_max(fmaxf(v0, v1));
-            s = wave_sum((e0 < hi ? __expf(v0 - m) : 0.0f) + (e1 < hi ? __expf(v1 - m) : 0.0f));
-        }
-        if (lane == 0)
-            wst[wave - 1] = make_float2(m, s);
-    }
-    __syncthreads();
-
-    // ---- wave 0 publishes the workgroup's partial result and takes the arrival ticket ----
-    if (wave == 0) {
-        const bool act = lane < 15;
-        float m = act ? wst[act ? lane : 0].x : neg_inf();
-        float s = act ? wst[act ? lane : 0].y : 0.0f;
-        wave_stat_merge(m, s, act);
-        const size_t slot = blockIdx.x;
-        if (lane < 16) {
-            st_dev(a.part_val + slot * 16 + lane, key2f(k64_key(best)));
-            st_dev(a.part_idx + slot * 16 + lane, k64_idx(best));
-        }
-        if (lane == 0) {
-            st_dev(reinterpret_cast<float*>(a.part_stat + slot), m);
-            st_dev(reinterpret_cast<float*>(a.part_stat + slot) + 1, s);
-        }
-        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the coherent stores are acknowledged
-        if (lane == 0) {
-            // arrival in two levels (groups of 16 workgroups, then the groups): at small V_draft all
-            // workgroups arrive within a fraction of a microsecond, and 256 atomics on one word
-            // queue up for longer than two uncontended round trips take.  Every counter is put back
-            // to zero by whoever sees it full.
-            const int grp = blockIdx.x >> 4;
-            const int ngrp = (gridDim.x + 15) >> 4;
-            const int in_grp = (grp == ngrp - 1) ? (int)gridDim.x - grp * 16 : 16;
-            int last = 0;
-            const unsigned int t1 =
-                __hip_atomic_fetch_add(a.arrive + (1 + grp) * kArriveStrideWords, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((int)t1 == in_grp - 1) {
-                __hip_atomic_store(a.arrive + (1 + grp) * kArriveStrideWords, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                const unsigned int t2 = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                last = ((int)t2 == ngrp - 1) ? 1 : 0;
-            }
-            s_last = last;
-        }
-    }
-    __syncthreads();
-    if (!s_last)
-        return;
-
-    // ---- the last workgroup to arrive finishes the call ----
-    k64* cand = reinterpret_cast<k64*>(lds + kLdsCand);
-    k64* wl2 = reinterpret_cast<k64*>(lds + kLdsWl2);
-    float2* fst = reinterpret_cast<float2*>(lds + kLdsFst);
-    const int P = gridDim.x;
-    {
-        // all lists into LDS as keys: thread t takes entries 4t .. 4t+3 with two 128-bit device-coherent
-        // loads, and one workgroup's statistics; every load is in flight before the first is awaited
-        // (lists beyond P are empty)
-        f32x4 v = {neg_inf(), neg_inf(), neg_inf(), neg_inf()};
-        i32x4 ix = {kIdxNone, kIdxNone, kIdxNone, kIdxNone};
-        float2 st = make_float2(neg_inf(), 0.0f);
-        const bool ok = tid < 4 * P;
-        const bool okp = tid < P;
-        if (ok) {
-            coherent_load_issue(v, a.part_val + 4 * tid);
-            coherent_load_issue(ix, a.part_idx + 4 * tid);
-        }
-        if (okp)
-            coherent_load_issue(st, a.part_stat + tid);
-        coherent_load_wait(v, ix, st);
-        float m = st.x, s = st.y;
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            cand[4 * tid + q] = k64_make(f2key(v[q]), ix[q]);
-        if (wave < 4) {  // the statistics of up to 256 workgroups sit in the first four waves
-            wave_stat_merge(m, s, okp);
-            if (lane == 0)
-                fst[wave] = make_float2(m, s);
-        }
-    }
-    __syncthreads();
-    {
-        const k64 mine = k64_merge_16_lists(cand + wave * 256, lane);  // wave w: lists 16w .. 16w+15
-        if (lane < 16)
-            wl2[wave * 16 + lane] = mine;
-    }
-    __syncthreads();
-    if (wave == 0) {
-        const k64 fin = k64_merge_16_lists(wl2, lane);
-        const bool act = lane < 4;
-        float mv = act ? fst[act ? lane : 0].x : neg_inf();
-        float sv = act ? fst[act ? lane : 0].y : 0.0f;
-        wave_stat_merge(mv, sv, act);
-        const float lse = mv + __logf(sv);
-        if (lane < a.k) {
-            const int oi = k64_idx(fin);
-            a.out_ids[lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
-            a.out_logp[lane] = key2f(k64_key(fin)) - lse;
-        }
-        if (lane == 0) {
-            if (a.lse_out != nullptr)
-                a.lse_out[0] = lse;
-            __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-    }
-}
-
-template <int T>
-static hipError_t launch_one_row_t(const Plan& p, const GemvArgs& ga, hipStream_t s)
-{
-    static_assert(kLdsTotal <= 48 * 1024, "fits the default dynamic LDS limit");
-    hipLaunchKernelGGL(gemv_one_row_kernel<T>, dim3(p.blocks), dim3(kGemvThreads), kLdsTotal, s, ga);
-    return hipGetLastError();
-}
-
 hipError_t launch_gemv_one_row(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
-    // what the kernel assumes: one row, lists of 16 in the workspace, H = 512 * T, at most 256
-    // workgroups (partial results) of at most kOneRowMaxRowsPerBlock W_sub rows each
-    if (ga.rows != 1 || ga.KP != 16 || ga.k > 16 || p.blocks > 256 || p.blocks < 1 || ga.P != p.blocks ||
-        (long long)ga.Vd > (long long)p.blocks * kOneRowMaxRowsPerBlock || !ga.fused)
+    if (!one_row_launch_ok(p, ga))
         return hipErrorInvalidValue;
-    switch (ga.nchunk) {
-    case 64: return launch_one_row_t<1>(p, ga, s);
-    case 128: return launch_one_row_t<2>(p, ga, s);
-    case 256: return launch_one_row_t<4>(p, ga, s);
-    case 512: return launch_one_row_t<8>(p, ga, s);
+    switch (ga.nchunk) {  // 16-byte pieces per row: H = 8 * nchunk = 512 * T
+    case 64: return launch_one_row_t<FmtBf16, 1>(p, ga, s);
+    case 128: return launch_one_row_t<FmtBf16, 2>(p, ga, s);
+    case 256: return launch_one_row_t<FmtBf16, 4>(p, ga, s);
+    case 512: return launch_one_row_t<FmtBf16, 8>(p, ga, s);
     }
     return hipErrorInvalidValue;
 }

@@ -3,6 +3,7 @@
 // the final merge that the last workgroup of a single-launch step runs.
 #pragma once
 
+#include "vt.h"
 #include "vt_device.h"
 #include "vt_internal.h"
 
@@ -14,6 +15,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 struct GemvArgs {
     const u32x4* h;
     const u32x4* W;
+    const void* scales;  // compressed W_sub only: fp32 per row (FP8) or exponent byte per 32 weights (MXFP4)
     int rows, nchunk, Vd, P, k, KP, rpb;  // rpb: W_sub rows per workgroup (multiple of J)
     int ks;  // slices of the hidden dimension whose partial logits sit side by side in LDS (1: none)
     float* part_val;
@@ -41,6 +43,8 @@ __device__ __forceinline__ float ld_dev(const float* p) { return __hip_atomic_lo
 __device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 hipError_t launch_gemv_one_row(const Plan& p, const GemvArgs& ga, hipStream_t s);
+hipError_t launch_gemv_one_row_q(int fmt, const Plan& p, const GemvArgs& ga, hipStream_t s);
+hipError_t launch_gemv_q(int fmt, const Plan& p, const HeadArgs& a, hipStream_t s);
 
 // Final merge by the last workgroup: the partial lists of every row are fetched into LDS (all
 // threads, coalesced), 256 threads per hidden-state row reduce the row's softmax partials, then

@@ -13,6 +13,7 @@ namespace vt {
 struct HeadArgs {
     const uint16_t* h;
     const uint16_t* W;
+    const void* scales;  // compressed W_sub only
     const int32_t* d2t;
     int32_t* out_ids;
     float* out_logp;
@@ -48,6 +49,8 @@ VT_DECL_GEMM_KP(64)
 hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_gemm(const Plan& p, const HeadArgs& a, hipStream_t s);
 hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s);
+hipError_t launch_quant_gather(int fmt, const uint16_t* W, int H, const int32_t* ids, int Vd, uint8_t* codes,
+                               void* scales, int32_t* d2t, hipStream_t s);
 hipError_t launch_clear_words(uint32_t* p, int n, hipStream_t s);
 hipError_t launch_check_ids(const int32_t* ids, int Vd, int V, uint32_t* bitmap, int* err, hipStream_t s);
 hipError_t launch_gather(const uint16_t* W, int H, const int32_t* ids, int Vd, uint16_t* W_sub, int32_t* d2t,

@@ -126,6 +126,19 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
     return true;
 }
 
+bool make_plan_q(int fmt, int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
+{
+    const bool h_ok = (fmt == VT_Q_FP8_E4M3 && (H == 1024 || H == 2048 || H == 4096)) ||
+                      (fmt == VT_Q_MXFP4 && (H == 2048 || H == 4096));
+    if (!h_ok || rows != 1 || k < 1 || k > 16 || Vd < 1 || Vd > (int64_t)kGemvTargetBlocks * kGemvWaves * 64)
+        return false;
+    // the one-row plan of the bf16 head with the same V_draft and k (the hidden size only selects the kernel)
+    if (!make_plan(1, 4096, Vd, k, p) || !p.one_row)
+        return false;
+    p.H = (int)H;
+    return true;
+}
+
 static bool shape_ok(int64_t rows, int64_t H, int64_t Vd)
 {
     const int64_t lim = (int64_t)1 << 31;
@@ -222,6 +235,32 @@ size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, i
         return 0;
     Plan p;
     if (!make_plan(rows, H, V_draft, k, p))
+        return 0;
+    return p.total_bytes;
+}
+
+size_t vt_subset_q_code_bytes(int fmt, int64_t V_draft, int64_t H)
+{
+    if (V_draft < 1 || H < 32 || V_draft >= ((int64_t)1 << 31) || H >= ((int64_t)1 << 31))
+        return 0;
+    if (fmt == VT_Q_FP8_E4M3 && H % 16 == 0)
+        return (size_t)V_draft * (size_t)H;
+    if (fmt == VT_Q_MXFP4 && H % 32 == 0)
+        return (size_t)V_draft * (size_t)H / 2;
+    return 0;
+}
+
+size_t vt_subset_q_scale_bytes(int fmt, int64_t V_draft, int64_t H)
+{
+    if (vt_subset_q_code_bytes(fmt, V_draft, H) == 0)
+        return 0;
+    return fmt == VT_Q_FP8_E4M3 ? (size_t)V_draft * sizeof(float) : (size_t)V_draft * (size_t)(H / 32);
+}
+
+size_t vt_draft_head_q_workspace_bytes(int fmt, int64_t rows, int64_t H, int64_t V_draft, int k)
+{
+    Plan p;
+    if (!make_plan_q(fmt, rows, H, V_draft, k, p))
         return 0;
     return p.total_bytes;
 }

@@ -51,6 +51,10 @@ struct Plan {
 // Fills `p`; returns false when the shape is not servable (caller has validated ranges).
 bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p);
 
+// The plan of a draft step over a compressed W_sub (format codes as in the C header); false when
+// the shape is not served.
+bool make_plan_q(int fmt, int64_t rows, int64_t H, int64_t Vd, int k, Plan& p);
+
 // GEMM tile shapes (vocab x rows per workgroup) and their partial counts.
 int gemm_pick_tile(int rows, int H, int Vd, int KP);
 void gemm_tile_dims(int tile, int& BMV, int& BNR, int& parts_per_vtile);
