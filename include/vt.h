@@ -158,6 +158,45 @@ vt_status vt_draft_head_debug(const uint16_t *h, int64_t rows, int64_t H, const 
                               float *logits_out, float *lse_out);
 
 /*
+ * The feature-fusion layer of the draft model (Section 2.3, component 1; Table 1's "Feature fusion"
+ * row, 2*3d*d FLOPs per row): g[r,j] = sum_i x[r,i] * W_fc[j,i], bf16 in, fp32 accumulation, one
+ * rounding to bf16 (nearest even).
+ *   x      device, [rows,d_in] bf16   (d_in = 3d: the three concatenated target features)
+ *   W_fc   device, [d_out,d_in] bf16
+ *   g_out  device, [rows,d_out] bf16, 8-byte aligned
+ * d_in % 8 == 0.  Asynchronous on `stream`, allocates nothing.
+ */
+vt_status vt_feature_fusion(const uint16_t *x, int64_t rows, int64_t d_in, const uint16_t *W_fc, int64_t d_out,
+                            uint16_t *g_out, void *stream);
+
+/*
+ * The draft step with its neighbours fused in: the hidden state arrives before the final
+ * normalisation and leaves as path scores of a draft tree.
+ *   h[r,i]      = bf16( g[r,i] * rsqrt(mean_i g[r,i]^2 + eps) * gamma[i] )   (root-mean-square norm; the
+ *                 paper names no normalisation: this is the LLaMA family's, in fp32, one rounding)
+ *   ids, logp   = vt_draft_head(h, ...)
+ *   out_scores[r,p] = logp[r,p] + parent_scores[r]   (cumulative log-probability of the path that the
+ *                 proposed token extends; parent_scores may be NULL: plain log-probabilities)
+ * For one row the normalisation happens while the hidden state is staged inside the step's single
+ * kernel (it never returns to memory); other row counts run a small kernel first.
+ *   g              device, [rows,H] bf16      gamma  device, [H] bf16, 8-byte aligned
+ *   parent_scores  device, [rows] fp32, or NULL
+ *   workspace      device, >= vt_draft_head_fused_workspace_bytes(...), initialised once as for vt_draft_head
+ * Everything else as vt_draft_head.  The _debug form also stores logits_out[rows,V_draft], lse_out[rows]
+ * and the normalised state h_out[rows,H] (each may be NULL).
+ */
+size_t vt_draft_head_fused_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k);
+vt_status vt_draft_head_fused(const uint16_t *g, const uint16_t *gamma, float eps, const float *parent_scores,
+                              int64_t rows, int64_t H, const uint16_t *W_sub, const int32_t *d2t, int64_t V_draft,
+                              int k, int32_t *out_target_ids, float *out_scores, void *workspace,
+                              size_t workspace_bytes, void *stream);
+vt_status vt_draft_head_fused_debug(const uint16_t *g, const uint16_t *gamma, float eps, const float *parent_scores,
+                                    int64_t rows, int64_t H, const uint16_t *W_sub, const int32_t *d2t, int64_t V_draft,
+                                    int k, int32_t *out_target_ids, float *out_scores, void *workspace,
+                                    size_t workspace_bytes, void *stream, float *logits_out, float *lse_out,
+                                    uint16_t *h_out);
+
+/*
  * Compressed W_sub for the one-row draft step.  Sections 1 and 2.3: the head dominates the
  * draft's latency and costs 2*d*k per token; at one row that is the bytes of W_sub, which
  * trimming cuts through k and a narrower storage format cuts per weight.  Two formats:

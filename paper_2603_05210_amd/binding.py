@@ -29,7 +29,8 @@ EXPORTS = (
     "vt_validate_build_subset_args", "vt_validate_draft_head_args", "vt_draft_head_workspace_bytes",
     "vt_draft_head_workspace_init", "vt_draft_head_regime", "vt_draft_head", "vt_draft_head_debug",
     "vt_draft_head_static", "vt_subset_q_code_bytes", "vt_subset_q_scale_bytes", "vt_build_subset_q",
-    "vt_draft_head_q_workspace_bytes", "vt_draft_head_q", "vt_draft_head_q_debug",
+    "vt_draft_head_q_workspace_bytes", "vt_draft_head_q", "vt_draft_head_q_debug", "vt_feature_fusion",
+    "vt_draft_head_fused_workspace_bytes", "vt_draft_head_fused", "vt_draft_head_fused_debug",
     "vt_select_vocab_workspace_bytes", "vt_validate_select_vocab_args",
     "vt_select_vocab", "vt_build_t2d", "vt_coverage_workspace_bytes", "vt_coverage",
 )
@@ -84,6 +85,14 @@ def lib() -> ctypes.CDLL:
         L.vt_draft_head_q.argtypes = [p, i64, i64, p, p, i32, p, i64, i32, p, p, p, sz, p]
         L.vt_draft_head_q_debug.restype = i32
         L.vt_draft_head_q_debug.argtypes = [p, i64, i64, p, p, i32, p, i64, i32, p, p, p, sz, p, p, p]
+        L.vt_feature_fusion.restype = i32
+        L.vt_feature_fusion.argtypes = [p, i64, i64, p, i64, p, p]
+        L.vt_draft_head_fused_workspace_bytes.restype = sz
+        L.vt_draft_head_fused_workspace_bytes.argtypes = [i64, i64, i64, i32]
+        L.vt_draft_head_fused.restype = i32
+        L.vt_draft_head_fused.argtypes = [p, p, ctypes.c_float, p, i64, i64, p, p, i64, i32, p, p, p, sz, p]
+        L.vt_draft_head_fused_debug.restype = i32
+        L.vt_draft_head_fused_debug.argtypes = [p, p, ctypes.c_float, p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p, p]
         L.vt_draft_head_debug.restype = i32
         L.vt_draft_head_debug.argtypes = [p, i64, i64, p, p, i64, i32, p, p, p, sz, p, p, p]
         L.vt_draft_head_workspace_init.restype = i32
@@ -259,6 +268,57 @@ def vt_draft_head_static(h: torch.Tensor, W_sub: torch.Tensor, d2t: torch.Tensor
     if st != VT_OK:
         raise VtError(st, "vt_draft_head_static")
     return out_target_ids, out_logprobs
+
+
+def vt_feature_fusion(x: torch.Tensor, W_fc: torch.Tensor, g_out: torch.Tensor | None = None) -> torch.Tensor:
+    """g[rows,d_out] = x[rows,d_in] . W_fc[d_out,d_in]^T (bf16 in and out, fp32 accumulation)."""
+    _dev16(x, "x")
+    _dev16(W_fc, "W_fc")
+    rows, d_in = x.shape
+    d_out, d_in2 = W_fc.shape
+    if d_in2 != d_in:
+        raise ValueError("shape mismatch between x and W_fc")
+    if g_out is None:
+        g_out = torch.empty((rows, d_out), dtype=x.dtype, device=x.device)
+    with torch.cuda.device(x.device):
+        st = lib().vt_feature_fusion(x.data_ptr(), rows, d_in, W_fc.data_ptr(), d_out, g_out.data_ptr(), _stream_ptr(x))
+    if st != VT_OK:
+        raise VtError(st, "vt_feature_fusion")
+    return g_out
+
+
+def vt_draft_head_fused_workspace_bytes(rows: int, H: int, V_draft: int, k: int) -> int:
+    return int(lib().vt_draft_head_fused_workspace_bytes(rows, H, V_draft, k))
+
+
+def vt_draft_head_fused(g: torch.Tensor, gamma: torch.Tensor, eps: float, W_sub: torch.Tensor, d2t: torch.Tensor, k: int,
+                        parent_scores: torch.Tensor | None = None, out_target_ids: torch.Tensor | None = None,
+                        out_scores: torch.Tensor | None = None, workspace: torch.Tensor | None = None,
+                        logits_out: torch.Tensor | None = None, lse_out: torch.Tensor | None = None,
+                        h_out: torch.Tensor | None = None):
+    """RMSNorm -> draft head -> path scores in one call: (target ids [rows,k], scores [rows,k])."""
+    _dev16(g, "g")
+    _dev16(gamma, "gamma")
+    _dev16(W_sub, "W_sub")
+    _devi32(d2t, "d2t")
+    rows, H = g.shape
+    Vd = W_sub.shape[0]
+    dev = g.device
+    if out_target_ids is None:
+        out_target_ids = torch.empty((rows, k), dtype=torch.int32, device=dev)
+    if out_scores is None:
+        out_scores = torch.empty((rows, k), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = new_workspace(vt_draft_head_fused_workspace_bytes(rows, H, Vd, k), dev)
+    opt = lambda t: None if t is None else t.data_ptr()
+    with torch.cuda.device(dev):
+        st = lib().vt_draft_head_fused_debug(g.data_ptr(), gamma.data_ptr(), float(eps), opt(parent_scores), rows, H,
+                                             W_sub.data_ptr(), d2t.data_ptr(), Vd, k, out_target_ids.data_ptr(),
+                                             out_scores.data_ptr(), workspace.data_ptr(), workspace.numel(),
+                                             _stream_ptr(g), opt(logits_out), opt(lse_out), opt(h_out))
+    if st != VT_OK:
+        raise VtError(st, "vt_draft_head_fused")
+    return out_target_ids, out_scores
 
 
 VT_Q_FP8_E4M3 = 1

@@ -19,17 +19,41 @@ static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 // The launch sequence of one draft step on validated arguments; `ws` is a workspace whose header
 // has been initialised (arrival counter zero).
+// What the variants of the step add to the plain call.
+struct HeadExtras {
+    int fmt = 0;                    // storage format of W_sub (0: bf16)
+    const void* scales = nullptr;   // compressed forms only
+    const uint16_t* gamma = nullptr;  // fused RMSNorm ahead of the head: weight [H], or NULL
+    float eps = 0.0f;
+    const float* parent = nullptr;  // per-row cumulative log-probability added to the outputs, or NULL
+    uint16_t* h_out = nullptr;      // test hook: normalised hidden state
+};
+
 static vt_status run_head(const uint16_t* h, int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t,
                           int64_t V_draft, int k, int32_t* out_target_ids, float* out_logprobs, char* ws,
-                          hipStream_t s, float* logits_out, float* lse_out, int fmt = 0, const void* scales = nullptr)
+                          hipStream_t s, float* logits_out, float* lse_out, const HeadExtras& ex = HeadExtras())
 {
+    const int fmt = ex.fmt;
     Plan p;
     if (!(fmt == 0 ? make_plan(rows, H, V_draft, k, p) : make_plan_q(fmt, rows, H, V_draft, k, p)))
         return VT_ERR_SHAPE;
     HeadArgs a;
     a.h = h;
     a.W = W_sub;
-    a.scales = scales;
+    a.scales = ex.scales;
+    a.gamma = ex.gamma;
+    a.eps = ex.eps;
+    a.parent = ex.parent;
+    a.h_out = ex.h_out;
+    if (ex.gamma != nullptr && !p.one_row) {
+        // only the one-row kernel normalises on the way in: the other shapes get a small kernel of
+        // their own, which leaves the normalised state behind the partial results in the workspace
+        uint16_t* hn = ex.h_out != nullptr ? ex.h_out : reinterpret_cast<uint16_t*>(ws + p.total_bytes);
+        if (launch_rmsnorm(h, ex.gamma, ex.eps, (int)rows, (int)H, hn, s) != hipSuccess)
+            return VT_ERR_DEVICE;
+        a.h = hn;
+        a.gamma = nullptr;
+    }
     a.d2t = d2t;
     a.out_ids = out_target_ids;
     a.out_logp = out_logprobs;
@@ -170,6 +194,67 @@ vt_status vt_draft_head_debug(const uint16_t* h, int64_t rows, int64_t H, const 
                     static_cast<hipStream_t>(stream), logits_out, lse_out);
 }
 
+vt_status vt_feature_fusion(const uint16_t* x, int64_t rows, int64_t d_in, const uint16_t* W_fc, int64_t d_out,
+                            uint16_t* g_out, void* stream)
+{
+    if (!x || !W_fc || !g_out)
+        return VT_ERR_NULL;
+    const int64_t lim = (int64_t)1 << 31;
+    if (rows < 1 || d_in < 8 || d_out < 1 || (d_in % 8) != 0 || rows >= lim || d_in >= lim || d_out >= lim ||
+        d_out * (d_in / 8) >= lim || rows * (d_in / 8) >= lim)
+        return VT_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(W_fc) || (reinterpret_cast<uintptr_t>(g_out) & 7u))
+        return VT_ERR_ALIGN;
+    if (launch_feature_fusion(x, (int)rows, (int)d_in, W_fc, (int)d_out, g_out, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return VT_ERR_DEVICE;
+    return VT_OK;
+}
+
+size_t vt_draft_head_fused_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, int k)
+{
+    const size_t head = vt_draft_head_workspace_bytes(rows, H, V_draft, k);
+    if (head == 0)
+        return 0;
+    return head + ((size_t)rows * (size_t)H * 2 + 255) / 256 * 256;  // room for the normalised state
+}
+
+vt_status vt_draft_head_fused_debug(const uint16_t* g, const uint16_t* gamma, float eps, const float* parent_scores,
+                                    int64_t rows, int64_t H, const uint16_t* W_sub, const int32_t* d2t, int64_t V_draft,
+                                    int k, int32_t* out_target_ids, float* out_scores, void* workspace,
+                                    size_t workspace_bytes, void* stream, float* logits_out, float* lse_out,
+                                    uint16_t* h_out)
+{
+    if (!gamma)
+        return VT_ERR_NULL;
+    if (!(eps >= 0.0f))
+        return VT_ERR_SHAPE;
+    vt_status st = vt_validate_draft_head_args(g, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_scores, workspace,
+                                               workspace_bytes);
+    if (st != VT_OK)
+        return st;
+    if (workspace_bytes < vt_draft_head_fused_workspace_bytes(rows, H, V_draft, k))
+        return VT_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(gamma) & 7u) || (reinterpret_cast<uintptr_t>(parent_scores) & 3u) ||
+        (reinterpret_cast<uintptr_t>(h_out) & 7u))
+        return VT_ERR_ALIGN;
+    HeadExtras ex;
+    ex.gamma = gamma;
+    ex.eps = eps;
+    ex.parent = parent_scores;
+    ex.h_out = h_out;
+    return run_head(g, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_scores, static_cast<char*>(workspace),
+                    static_cast<hipStream_t>(stream), logits_out, lse_out, ex);
+}
+
+vt_status vt_draft_head_fused(const uint16_t* g, const uint16_t* gamma, float eps, const float* parent_scores, int64_t rows,
+                              int64_t H, const uint16_t* W_sub, const int32_t* d2t, int64_t V_draft, int k,
+                              int32_t* out_target_ids, float* out_scores, void* workspace, size_t workspace_bytes,
+                              void* stream)
+{
+    return vt_draft_head_fused_debug(g, gamma, eps, parent_scores, rows, H, W_sub, d2t, V_draft, k, out_target_ids, out_scores,
+                                     workspace, workspace_bytes, stream, nullptr, nullptr, nullptr);
+}
+
 vt_status vt_draft_head_q_debug(const uint16_t* h, int64_t rows, int64_t H, const uint8_t* codes, const void* scales,
                                 int fmt, const int32_t* d2t, int64_t V_draft, int k, int32_t* out_target_ids,
                                 float* out_logprobs, void* workspace, size_t workspace_bytes, void* stream,
@@ -188,8 +273,11 @@ vt_status vt_draft_head_q_debug(const uint16_t* h, int64_t rows, int64_t H, cons
         (reinterpret_cast<uintptr_t>(d2t) & 3u) || (reinterpret_cast<uintptr_t>(out_target_ids) & 3u) ||
         (reinterpret_cast<uintptr_t>(out_logprobs) & 3u))
         return VT_ERR_ALIGN;
+    HeadExtras ex;
+    ex.fmt = fmt;
+    ex.scales = scales;
     return run_head(h, rows, H, reinterpret_cast<const uint16_t*>(codes), d2t, V_draft, k, out_target_ids, out_logprobs,
-                    static_cast<char*>(workspace), static_cast<hipStream_t>(stream), logits_out, lse_out, fmt, scales);
+                    static_cast<char*>(workspace), static_cast<hipStream_t>(stream), logits_out, lse_out, ex);
 }
 
 vt_status vt_draft_head_q(const uint16_t* h, int64_t rows, int64_t H, const uint8_t* codes, const void* scales, int fmt,

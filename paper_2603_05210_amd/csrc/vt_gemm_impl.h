@@ -209,7 +209,44 @@ __device__ __forceinline__ void head_epilogue(f32x16 (&acc)[SV * SR], const Gemm
     });
 }
 
-template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K>
+// Projection-only epilogue (the feature-fusion layer of Section 2.3): the tile of the product
+// goes to memory as bf16 (round to nearest even), row-major [rows][Vd]; a lane stores runs of four
+// consecutive outputs of its row.
+template <int WV, int WR, int SV, int SR>
+__device__ __forceinline__ void store_epilogue(f32x16 (&acc)[SV * SR], const GemmArgs& a, int v0, int r0, int wave, int lane)
+{
+    const int wv = wave / WR;
+    const int wr = wave - wv * WR;
+    const int frow = lane & 31;
+    const int fhalf = lane >> 5;
+    static_for<SR>([&](auto Jc) {
+        constexpr int sr = decltype(Jc)::value;
+        const int row = r0 + wr * SR * 32 + sr * 32 + frow;
+        if (row < a.rows) {
+            static_for<SV>([&](auto I) {
+                constexpr int sv = decltype(I)::value;
+                static_for<4>([&](auto Q) {
+                    constexpr int q = decltype(Q)::value;
+                    const int tok = v0 + wv * SV * 32 + sv * 32 + 8 * q + 4 * fhalf;
+                    uint16_t* dst = a.store_out + (size_t)row * a.Vd + tok;
+                    if (tok + 3 < a.Vd && (a.Vd & 3) == 0) {
+                        const uint32_t lo = f32_to_bf16_bits(acc[sv * SR + sr][4 * q]) | (f32_to_bf16_bits(acc[sv * SR + sr][4 * q + 1]) << 16);
+                        const uint32_t hi = f32_to_bf16_bits(acc[sv * SR + sr][4 * q + 2]) | (f32_to_bf16_bits(acc[sv * SR + sr][4 * q + 3]) << 16);
+                        *reinterpret_cast<uint2*>(dst) = make_uint2(lo, hi);
+                    } else {
+                        static_for<4>([&](auto C) {
+                            constexpr int c = decltype(C)::value;
+                            if (tok + c < a.Vd)
+                                dst[c] = (uint16_t)f32_to_bf16_bits(acc[sv * SR + sr][4 * q + c]);
+                        });
+                    }
+                });
+            });
+        }
+    });
+}
+
+template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K, bool STORE = false>
 __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
 {
     constexpr int BMV = WV * SV * 32;    // draft tokens per workgroup tile
@@ -417,10 +454,13 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
         k_tile(kt, std::false_type{}, std::false_type{});
     }
 
-    head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
+    if constexpr (STORE)
+        store_epilogue<WV, WR, SV, SR>(acc, a, v0, r0, wave, lane);
+    else
+        head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
 }
 
-template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD>
+template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD, bool STORE = false>
 static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
 {
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
@@ -430,10 +470,10 @@ static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
     constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
     const bool guard = (p.H % 64) != 0;
-    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false>;
+    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false, STORE>;
     if constexpr (ALLOW_GUARD) {
         if (guard)
-            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true>;
+            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true, STORE>;
     } else {
         if (guard)
             return hipErrorInvalidValue;

@@ -500,6 +500,10 @@ static void fill_gemv_args(const Plan& p, const HeadArgs& a, GemvArgs& ga)
     ga.h = reinterpret_cast<const u32x4*>(a.h);
     ga.W = reinterpret_cast<const u32x4*>(a.W);
     ga.scales = a.scales;
+    ga.gamma = a.gamma;
+    ga.eps = a.eps;
+    ga.parent = a.parent;
+    ga.h_out = a.h_out;
     ga.rows = p.rows;
     ga.nchunk = p.H / 8;
     ga.Vd = p.Vd;

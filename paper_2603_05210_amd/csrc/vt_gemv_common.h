@@ -16,6 +16,10 @@ struct GemvArgs {
     const u32x4* h;
     const u32x4* W;
     const void* scales;  // compressed W_sub only: fp32 per row (FP8) or exponent byte per 32 weights (MXFP4)
+    const uint16_t* gamma;  // fused RMSNorm weight, or NULL
+    float eps;
+    const float* parent;    // per-row score added to the emitted log-probabilities, or NULL
+    uint16_t* h_out;        // test hook: normalised hidden state, or NULL
     int rows, nchunk, Vd, P, k, KP, rpb;  // rpb: W_sub rows per workgroup (multiple of J)
     int ks;  // slices of the hidden dimension whose partial logits sit side by side in LDS (1: none)
     float* part_val;
@@ -98,7 +102,7 @@ __device__ __forceinline__ void fused_final_merge(const GemvArgs& a, char* lds, 
         const float lse = mv + __logf(sv);
         if (lane < a.k) {
             a.out_ids[(size_t)row * a.k + lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
-            a.out_logp[(size_t)row * a.k + lane] = ov - lse;
+            a.out_logp[(size_t)row * a.k + lane] = (ov - lse) + (a.parent != nullptr ? a.parent[row] : 0.0f);
         }
         if (lane == 0 && a.lse_out != nullptr)
             a.lse_out[row] = lse;

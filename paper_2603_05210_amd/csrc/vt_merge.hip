@@ -20,7 +20,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                                                               int lists_sorted, const int32_t* __restrict__ d2t,
                                                               int32_t* __restrict__ out_ids,
                                                               float* __restrict__ out_logp,
-                                                              float* __restrict__ lse_out)
+                                                              float* __restrict__ lse_out,
+                                                              const float* __restrict__ parent)
 {
     constexpr int NW = kMergeThreads / kWave;
     __shared__ float sm_val[KP > 16 ? NW : 1][KP];  // per-wave results (long lists only)
@@ -226,7 +227,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         const float lse = mv + __logf(sv);
         if (lane < k) {
             out_ids[(size_t)r * k + lane] = (oi != kIdxNone) ? d2t[oi] : -1;
-            out_logp[(size_t)r * k + lane] = ov - lse;
+            out_logp[(size_t)r * k + lane] = (ov - lse) + (parent != nullptr ? parent[r] : 0.0f);
         }
         if (lane == 0 && lse_out != nullptr)
             lse_out[r] = lse;
@@ -240,7 +241,7 @@ hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s)
 #define VT_MERGE_CASE(KPV)                                                                                   \
     case KPV:                                                                                                \
         hipLaunchKernelGGL(merge_kernel<KPV>, dim3(p.rows), dim3(kMergeThreads), 0, s, a.part_val, a.part_idx, \
-                           a.part_stat, p.P, p.k, sorted, a.d2t, a.out_ids, a.out_logp, a.lse_out);          \
+                           a.part_stat, p.P, p.k, sorted, a.d2t, a.out_ids, a.out_logp, a.lse_out, a.parent);  \
         break;
     switch (p.KP) {
         VT_MERGE_CASE(1)
@@ -254,6 +255,42 @@ hipError_t launch_merge(const Plan& p, const HeadArgs& a, hipStream_t s)
         return hipErrorInvalidValue;
     }
 #undef VT_MERGE_CASE
+    return hipGetLastError();
+}
+
+// RMSNorm of the hidden states ahead of the head, for the shapes whose projection kernel does not
+// normalise on the way in: h[r,i] = bf16(g[r,i] * rsqrt(mean_i g[r,i]^2 + eps) * gamma[i]); one
+// workgroup per row, sums in a fixed order.
+__global__ void __launch_bounds__(256) rmsnorm_kernel(const uint32_t* __restrict__ g, const uint32_t* __restrict__ gamma,
+                                                      float eps, int H, uint32_t* __restrict__ h_out)
+{
+    __shared__ float part[4];
+    const int r = blockIdx.x;
+    const int tid = threadIdx.x;
+    const uint32_t* gr = g + (size_t)r * (H / 2);
+    float ss = 0.0f;
+    for (int c = tid; c < H / 2; c += 256) {
+        const uint32_t w = gr[c];
+        const float a = bf16_lo(w), b = bf16_hi(w);
+        ss += a * a + b * b;
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0)
+        part[tid >> 6] = ss;
+    __syncthreads();
+    const float tot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float rs = 1.0f / __builtin_sqrtf(tot / (float)H + eps);
+    for (int c = tid; c < H / 2; c += 256) {
+        const uint32_t w = gr[c], gm = gamma[c];
+        const float a = (bf16_lo(w) * rs) * bf16_lo(gm), b = (bf16_hi(w) * rs) * bf16_hi(gm);
+        h_out[(size_t)r * (H / 2) + c] = f32_to_bf16_bits(a) | (f32_to_bf16_bits(b) << 16);
+    }
+}
+
+hipError_t launch_rmsnorm(const uint16_t* g, const uint16_t* gamma, float eps, int rows, int H, uint16_t* h_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(rmsnorm_kernel, dim3(rows), dim3(256), 0, s, reinterpret_cast<const uint32_t*>(g),
+                       reinterpret_cast<const uint32_t*>(gamma), eps, H, reinterpret_cast<uint32_t*>(h_out));
     return hipGetLastError();
 }
 

@@ -193,7 +193,11 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
 
     // the hidden state: one 8-byte piece (four bf16) per thread, requested before anything else
     const int hpiece = tid < H / 4 ? tid : H / 4 - 1;
-    const uint2 hval = reinterpret_cast<const uint2*>(a.h)[hpiece];
+    uint2 hval = reinterpret_cast<const uint2*>(a.h)[hpiece];
+    const bool norm = a.gamma != nullptr;  // h is the state before the final RMSNorm: normalise it on the way in
+    uint2 gval = make_uint2(0u, 0u);
+    if (norm)
+        gval = reinterpret_cast<const uint2*>(a.gamma)[hpiece];
     __builtin_amdgcn_sched_barrier(0);
     // the first hand-out is the wave's own number; later ones come from the counter
     if (tid == 0)
@@ -209,6 +213,29 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
     // __syncthreads would drain the W_sub loads in flight.
     uint32_t hreg[T * HR];
     auto stage_h = [&]() {
+        if (norm) {
+            // RMSNorm on the way in: every thread squares its four elements, the 16 wave sums meet in LDS
+            // and every thread adds them up in the same order; h = bf16(g * rsqrt(mean g^2 + eps) * gamma)
+            const float g0 = bf16_lo(hval.x), g1 = bf16_hi(hval.x), g2 = bf16_lo(hval.y), g3 = bf16_hi(hval.y);
+            float ss = tid < H / 4 ? ((g0 * g0 + g1 * g1) + (g2 * g2 + g3 * g3)) : 0.0f;
+            ss = wave_sum(ss);
+            float* nrm = reinterpret_cast<float*>(lds + kLdsWst);
+            if (lane == 0)
+                nrm[wave] = ss;
+            __builtin_amdgcn_s_waitcnt(0xC07F);
+            __builtin_amdgcn_s_barrier();
+            float tot = 0.0f;
+#pragma unroll
+            for (int w = 0; w < kGemvWaves; ++w)
+                tot += nrm[w];
+            const float r = 1.0f / __builtin_sqrtf(tot / (float)H + a.eps);
+            const float n0 = (g0 * r) * bf16_lo(gval.x), n1 = (g1 * r) * bf16_hi(gval.x);
+            const float n2 = (g2 * r) * bf16_lo(gval.y), n3 = (g3 * r) * bf16_hi(gval.y);
+            hval = make_uint2(f32_to_bf16_bits(n0) | (f32_to_bf16_bits(n1) << 16),
+                              f32_to_bf16_bits(n2) | (f32_to_bf16_bits(n3) << 16));
+            if (a.h_out != nullptr && blockIdx.x == 0 && tid < H / 4)
+                reinterpret_cast<uint2*>(a.h_out)[tid] = hval;
+        }
         reinterpret_cast<uint2*>(lds + kLdsH)[hpiece] = hval;
         __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
         __builtin_amdgcn_s_barrier();        // every wave passes exactly one of the two barriers below
@@ -428,7 +455,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
         if (lane < a.k) {
             const int oi = k64_idx(fin);
             a.out_ids[lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
-            a.out_logp[lane] = key2f(k64_key(fin)) - lse;
+            a.out_logp[lane] = (key2f(k64_key(fin)) - lse) + (a.parent != nullptr ? a.parent[0] : 0.0f);
         }
         if (lane == 0) {
             if (a.lse_out != nullptr)
