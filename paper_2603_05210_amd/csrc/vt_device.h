@@ -370,6 +370,90 @@ __device__ __forceinline__ void wave_walk_merge(const float* lv, const int* li, 
     outv = key2f(outk);
 }
 
+// ---- 64-bit order keys: a candidate (logit, draft index) as one integer, larger = better ----
+// high word: the order-preserving key of the logit; low word: 0x7fffffff - index, so that of
+// two equal logits the lower index is the larger key.  Distinct candidates have distinct keys
+// (the empty marker, key of -inf with index kIdxNone, is the smallest of all and may repeat).
+typedef long long k64;
+__device__ __forceinline__ k64 k64_make(int key, int idx)
+{
+    return (k64)(((unsigned long long)(unsigned int)key << 32) | (unsigned int)(kIdxNone - idx));
+}
+__device__ __forceinline__ int k64_key(k64 x) { return (int)(x >> 32); }
+__device__ __forceinline__ int k64_idx(k64 x) { return kIdxNone - (int)(unsigned int)x; }
+
+__device__ __forceinline__ k64 k64_row_mirror(k64 x)  // lane q of a 16-lane row <- lane 15-q
+{
+    const int lo = __builtin_amdgcn_mov_dpp((int)(unsigned int)x, 0x140, 0xf, 0xf, true);
+    const int hi = __builtin_amdgcn_mov_dpp((int)(x >> 32), 0x140, 0xf, 0xf, true);
+    return (k64)(((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo);
+}
+template <int OFF>
+__device__ __forceinline__ k64 k64_xchg(k64 x, int lane)  // value of lane l ^ OFF
+{
+    const int lo = xchg_i<OFF>((int)(unsigned int)x, lane);
+    const int hi = xchg_i<OFF>((int)(x >> 32), lane);
+    return (k64)(((unsigned long long)(unsigned int)hi << 32) | (unsigned int)lo);
+}
+// One stage of the bitonic sorter inside a 16-lane row: the lower lane of a pair keeps the
+// larger key.
+template <int OFF>
+__device__ __forceinline__ k64 k64_stage(k64 c, int lane)
+{
+    const k64 p = k64_xchg<OFF>(c, lane);
+    const bool lower = (lane & OFF) == 0;
+    return ((p > c) == lower) ? p : c;
+}
+// a, b: lists of 16 keys sorted best first, one per 16-lane row (lane q holds the q-th).
+// Returns the 16 best of their union, sorted best first: max(a, reversed b) is a bitonic
+// sequence holding exactly those 16, which four compare-exchange stages sort.
+__device__ __forceinline__ k64 k64_merge16(k64 a, k64 b, int lane)
+{
+    const k64 br = k64_row_mirror(b);
+    k64 c = a > br ? a : br;
+    c = k64_stage<8>(c, lane);
+    c = k64_stage<4>(c, lane);
+    c = k64_stage<2>(c, lane);
+    c = k64_stage<1>(c, lane);
+    return c;
+}
+// 16 sorted lists of 16 keys, stored back to back at `lists` (LDS), merged by one wave: every
+// 16-lane row returns the 16 best of all 256, sorted best first.
+__device__ __forceinline__ k64 k64_merge_16_lists(const k64* lists, int lane)
+{
+    const k64 s0 = lists[lane], s1 = lists[64 + lane], s2 = lists[128 + lane], s3 = lists[192 + lane];
+    const k64 m01 = k64_merge16(s0, s1, lane);
+    const k64 m23 = k64_merge16(s2, s3, lane);
+    k64 m = k64_merge16(m01, m23, lane);          // row r now holds the best of lists r, 4+r, 8+r, 12+r
+    m = k64_merge16(m, k64_xchg<16>(m, lane), lane);  // rows 0|1 and 2|3
+    m = k64_merge16(m, k64_xchg<32>(m, lane), lane);  // all four rows
+    return m;
+}
+
+// Sorts the 16 keys of every 16-lane row best first (bitonic sorting network, ten stages).
+template <int S, int OFF>
+__device__ __forceinline__ k64 k64_sort_stage(k64 c, int lane)
+{
+    const k64 p = k64_xchg<OFF>(c, lane);
+    const bool lower = (lane & OFF) == 0;
+    const bool desc = (lane & S) == 0 || S == 16;  // blocks alternate direction until the last pass
+    return ((p > c) == (lower == desc)) ? p : c;
+}
+__device__ __forceinline__ k64 k64_row_sort16(k64 c, int lane)
+{
+    c = k64_sort_stage<2, 1>(c, lane);
+    c = k64_sort_stage<4, 2>(c, lane);
+    c = k64_sort_stage<4, 1>(c, lane);
+    c = k64_sort_stage<8, 4>(c, lane);
+    c = k64_sort_stage<8, 2>(c, lane);
+    c = k64_sort_stage<8, 1>(c, lane);
+    c = k64_sort_stage<16, 8>(c, lane);
+    c = k64_sort_stage<16, 4>(c, lane);
+    c = k64_sort_stage<16, 2>(c, lane);
+    c = k64_sort_stage<16, 1>(c, lane);
+    return c;
+}
+
 // ---- the same reduction inside one DPP row (16 consecutive lanes), DPP only ----
 __device__ __forceinline__ float row16_max(float x) { return key2f(row16_max_i(f2key(x))); }
 

@@ -28,6 +28,11 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
     __shared__ int sm_idx[KP > 16 ? NW : 1][KP];
     __shared__ float2 sm_stat[NW];
     __shared__ int sm_qn;  // lists queued for the merge (short lists only)
+    // one LDS area, two uses: the surviving lists as 64-bit keys (up to kNetLists lists of 16, plus 16
+    // group results), or, when more lists survive, the per-thread sorted lists of the walking merge
+    constexpr int kNetLists = 256;
+    constexpr size_t kRawBytes = KP <= 16 ? ((kNetLists + 16) * 16 * 8 > kMergeThreads * (KP + 1) * 8 ? (kNetLists + 16) * 16 * 8 : kMergeThreads * (KP + 1) * 8) : 16;
+    __shared__ __align__(16) unsigned char sm_raw[kRawBytes];
 
     const int r = blockIdx.x;
     const int tid = threadIdx.x;
@@ -151,6 +156,76 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
             offer(p, part_stat[(size_t)r * P + p].x);
         __syncthreads();
         const int qn = sm_qn < QCAP ? sm_qn : QCAP;
+        if (sm_qn <= kNetLists) {
+            // The usual case: at most 256 lists survive the bound.  They go to LDS as 64-bit order keys,
+            // 16 per list (shorter lists padded with the empty marker), are sorted four at a time by
+            // a wave (one list per 16-lane row) unless they arrive sorted, and are merged by the same
+            // bitonic network as in the one-row kernel: groups of 16 lists per wave, then the group
+            // results by wave 0.  No rounds, no data-dependent control flow.
+            k64* sk = reinterpret_cast<k64*>(sm_raw);                 // [up to 256 lists][16]
+            k64* res = sk + kNetLists * 16;                          // [16 groups][16]
+            const int ngrp = (qn + 15) >> 4;
+            for (int q = tid; q < ngrp * 16; q += kMergeThreads) {
+                k64 e[16];
+#pragma unroll
+                for (int t = 0; t < 16; ++t)
+                    e[t] = k64_make(kKeyNone, kIdxNone);
+                if (q < qn) {
+                    const size_t slot = (size_t)r * P + sm_queue[q];
+                    const float* pv = part_val + slot * KP;
+                    const int32_t* pi = part_idx + slot * KP;
+                    if constexpr (KP % 4 == 0) {
+#pragma unroll
+                        for (int t = 0; t < KP; t += 4) {
+                            const float4 xv = *reinterpret_cast<const float4*>(pv + t);
+                            const int4 xi = *reinterpret_cast<const int4*>(pi + t);
+                            e[t] = k64_make(f2key(xv.x), xi.x), e[t + 1] = k64_make(f2key(xv.y), xi.y);
+                            e[t + 2] = k64_make(f2key(xv.z), xi.z), e[t + 3] = k64_make(f2key(xv.w), xi.w);
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < KP; ++t)
+                            e[t] = k64_make(f2key(pv[t]), pi[t]);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 16; ++t)
+                    sk[q * 16 + t] = e[t];
+            }
+            for (int q = tid; q < 256; q += kMergeThreads)  // unused group results are empty lists
+                res[q] = k64_make(kKeyNone, kIdxNone);
+            __syncthreads();
+            if (!lists_sorted) {
+                for (int g4 = wave; g4 * 4 < ngrp * 16; g4 += NW)
+                    sk[g4 * 64 + lane] = k64_row_sort16(sk[g4 * 64 + lane], lane);
+                __syncthreads();
+            }
+            for (int g = wave; g < ngrp; g += NW) {
+                const k64 m16 = k64_merge_16_lists(sk + g * 256, lane);
+                if (lane < 16)
+                    res[g * 16 + lane] = m16;
+            }
+            wave_stat_merge(m, s, true);
+            if (lane == 0)
+                sm_stat[wave] = make_float2(m, s);
+            __syncthreads();
+            if (wave != 0)
+                return;
+            const k64 fin = ngrp > 1 ? k64_merge_16_lists(res, lane) : res[lane & 15];
+            const bool act = lane < NW;
+            float mv = act ? sm_stat[act ? lane : 0].x : neg_inf();
+            float sv = act ? sm_stat[act ? lane : 0].y : 0.0f;
+            wave_stat_merge(mv, sv, act);
+            const float lse = mv + __logf(sv);
+            if (lane < k) {
+                const int oi = k64_idx(fin);
+                out_ids[(size_t)r * k + lane] = (oi != kIdxNone) ? d2t[oi] : -1;
+                out_logp[(size_t)r * k + lane] = (key2f(k64_key(fin)) - lse) + (parent != nullptr ? parent[r] : 0.0f);
+            }
+            if (lane == 0 && lse_out != nullptr)
+                lse_out[r] = lse;
+            return;
+        }
         for (int q = tid; q < qn; q += kMergeThreads)
             take_list(sm_queue[q]);
     } else {
@@ -176,8 +251,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
         // Every thread parks its (sorted) list in LDS; wave 0 merges all of them in k rounds,
         // touching only list heads.
         constexpr int S = KP + 1;
-        __shared__ float sl_val[kMergeThreads * S];
-        __shared__ int sl_idx[kMergeThreads * S];
+        float* sl_val = reinterpret_cast<float*>(sm_raw);  // [kMergeThreads][S]
+        int* sl_idx = reinterpret_cast<int*>(sm_raw) + kMergeThreads * S;
         sl_val[tid * S] = L.v[0];
         sl_idx[tid * S] = L.i[0];
         if (L.i[0] != kIdxNone) {
