@@ -31,7 +31,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
     // one LDS area, two uses: the surviving lists as 64-bit keys (up to kNetLists lists of 16, plus 16
     // group results), or, when more lists survive, the per-thread sorted lists of the walking merge
     constexpr int kNetLists = 256;
-    constexpr size_t kRawBytes = KP <= 16 ? ((kNetLists + 16) * 16 * 8 > kMergeThreads * (KP + 1) * 8 ? (kNetLists + 16) * 16 * 8 : kMergeThreads * (KP + 1) * 8) : 16;
+    constexpr size_t kRawBytes = KP < 16 ? kMergeThreads * (KP + 1) * 8 : KP == 16 ? ((kNetLists + 16) * 16 * 8 > kMergeThreads * (KP + 1) * 8 ? (kNetLists + 16) * 16 * 8 : kMergeThreads * (KP + 1) * 8) : 16;
     __shared__ __align__(16) unsigned char sm_raw[kRawBytes];
 
     const int r = blockIdx.x;
@@ -156,7 +156,7 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
             offer(p, part_stat[(size_t)r * P + p].x);
         __syncthreads();
         const int qn = sm_qn < QCAP ? sm_qn : QCAP;
-        if (sm_qn <= kNetLists) {
+        if (KP == 16 && sm_qn <= kNetLists) {  // measured: shorter lists are faster through the register sort + walking merge below
             // The usual case: at most 256 lists survive the bound.  They go to LDS as 64-bit order keys,
             // 16 per list (shorter lists padded with the empty marker), are sorted four at a time by
             // a wave (one list per 16-lane row) unless they arrive sorted, and are merged by the same
@@ -166,10 +166,8 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
             k64* res = sk + kNetLists * 16;                          // [16 groups][16]
             const int ngrp = (qn + 15) >> 4;
             for (int q = tid; q < ngrp * 16; q += kMergeThreads) {
-                k64 e[16];
-#pragma unroll
-                for (int t = 0; t < 16; ++t)
-                    e[t] = k64_make(kKeyNone, kIdxNone);
+                const k64 none = k64_make(kKeyNone, kIdxNone);
+                k64* dst = sk + q * 16;
                 if (q < qn) {
                     const size_t slot = (size_t)r * P + sm_queue[q];
                     const float* pv = part_val + slot * KP;
@@ -179,21 +177,24 @@ __global__ void __launch_bounds__(kMergeThreads) merge_kernel(const float* __res
                         for (int t = 0; t < KP; t += 4) {
                             const float4 xv = *reinterpret_cast<const float4*>(pv + t);
                             const int4 xi = *reinterpret_cast<const int4*>(pi + t);
-                            e[t] = k64_make(f2key(xv.x), xi.x), e[t + 1] = k64_make(f2key(xv.y), xi.y);
-                            e[t + 2] = k64_make(f2key(xv.z), xi.z), e[t + 3] = k64_make(f2key(xv.w), xi.w);
+                            dst[t] = k64_make(f2key(xv.x), xi.x), dst[t + 1] = k64_make(f2key(xv.y), xi.y);
+                            dst[t + 2] = k64_make(f2key(xv.z), xi.z), dst[t + 3] = k64_make(f2key(xv.w), xi.w);
                         }
                     } else {
 #pragma unroll
                         for (int t = 0; t < KP; ++t)
-                            e[t] = k64_make(f2key(pv[t]), pi[t]);
+                            dst[t] = k64_make(f2key(pv[t]), pi[t]);
                     }
-                }
 #pragma unroll
-                for (int t = 0; t < 16; ++t)
-                    sk[q * 16 + t] = e[t];
+                    for (int t = KP; t < 16; ++t)
+                        dst[t] = none;
+                } else {
+#pragma unroll
+                    for (int t = 0; t < 16; ++t)
+                        dst[t] = none;
+                }
             }
-            for (int q = tid; q < 256; q += kMergeThreads)  // unused group results are empty lists
-                res[q] = k64_make(kKeyNone, kIdxNone);
+            res[tid] = k64_make(kKeyNone, kIdxNone);  // unused group results are empty lists (256 entries, 256 threads)
             __syncthreads();
             if (!lists_sorted) {
                 for (int g4 = wave; g4 * 4 < ngrp * 16; g4 += NW)
