@@ -55,6 +55,10 @@ def parse_args():
                          "FETCH_SIZE / WRITE_SIZE profiler counters)")
     ap.add_argument("--select", action="store_true",
                     help="measure only the vocabulary-size selection call and exit")
+    ap.add_argument("--operands", choices=("gaussian", "zero_h", "const"), default="gaussian",
+                    help="operand values of the head workloads (same shapes, same kernels): the seeded Gaussian inputs, "
+                         "a zero hidden state, or constant W_sub and h -- how much of the matrix-core regime's time is "
+                         "the data toggling the datapath rather than the schedule")
     ap.add_argument("--shape", type=str, default=None,
                     help="rows,H,V_draft,k: run this shape as the headline instead (exploration)")
     return ap.parse_args()
@@ -73,11 +77,22 @@ def workloads():
         w.append(dict(name="cfg1_B%d" % b, H=2048, rows=b, Vd=V, k=10, peaked=0.0))
     w.append(dict(name="cfg3", H=4096, rows=1024, Vd=32000, k=8, peaked=0.0))
     w.append(dict(name="cfg4", H=4096, rows=512, Vd=V, k=16, peaked=0.05))
+    # the one-row step over a compressed W_sub, with its neighbours fused in, and the fusion layer ahead of it
+    for vd in (13264, V):
+        w.append(dict(name="fp8_Vd%d" % vd, kind="head_q", fmt=1, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
+        w.append(dict(name="mxfp4_Vd%d" % vd, kind="head_q", fmt=2, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
+    w.append(dict(name="fused_Vd13264", kind="head_fused", H=4096, rows=1, Vd=13264, k=10, peaked=0.0))
+    w.append(dict(name="fusion_B1", kind="fusion", H=4096, rows=1, Vd=4096, k=1, peaked=0.0))
+    w.append(dict(name="fusion_B64", kind="fusion", H=4096, rows=64, Vd=4096, k=1, peaked=0.0))
+    for x in w:
+        x.setdefault("kind", "head")
     return w
 
 
 def describe(w):
     from paper_2603_05210_amd.synth import FULL_VOCAB as V
+    if w.get("kind") == "fusion":
+        return "%s: feature-fusion projection rows=%d d_in=%d d_out=%d" % (w["name"], w["rows"], 3 * w["H"], w["H"])
     kind = "untrimmed head, identity d2t" if w["Vd"] == V else "Zipf(1.1)-ranked draft vocabulary of a %d-token head" % V
     return "%s: rows=%d H=%d V_draft=%d k=%d (%s)" % (w["name"], w["rows"], w["H"], w["Vd"], w["k"], kind)
 
@@ -85,7 +100,14 @@ def describe(w):
 def algorithmic(w):
     """Algorithmic bytes and FLOPs of one step's projection kernel."""
     H, R, Vd, k = w["H"], w["rows"], w["Vd"], w["k"]
-    nbytes = 2 * H * Vd + 2 * R * H + 4 * k * R + 8 * k * R
+    kind = w.get("kind", "head")
+    if kind == "fusion":           # g = x . W_fc^T with d_in = 3H, d_out = H (Section 2.3: 2*3d*d FLOPs per row)
+        return 2 * 3 * H * H + 2 * R * 3 * H + 2 * R * H, 2 * R * 3 * H * H
+    wbytes = 2 * H * Vd
+    if kind == "head_q":           # codes + scales
+        wbytes = H * Vd + 4 * Vd if w["fmt"] == 1 else H * Vd // 2 + (H // 32) * Vd
+    extra = 2 * H + 4 * R if kind == "head_fused" else 0     # gamma, parent scores
+    nbytes = wbytes + 2 * R * H + 4 * k * R + 8 * k * R + extra
     flops = 2 * R * H * Vd
     return nbytes, flops
 
@@ -102,6 +124,7 @@ class Runner:
         self.torch, self.vt, self.synth, self.dev = torch, vt, synth, dev
         self.W_host = {}
         self.W_dev = {}
+        self.operands = "gaussian"
 
     def full_W(self, H):
         import numpy as np
@@ -115,31 +138,68 @@ class Runner:
         self.W_host.pop(H, None)
         self.W_dev.pop(H, None)
 
+    def prepare_fusion(self, w):
+        import numpy as np
+        torch, vt, synth = self.torch, self.vt, self.synth
+        d = w["H"]
+        x = synth.gen_h(0, w["rows"], 3 * d)
+        Wfc = synth.gen_W(7, d, 3 * d)
+        to_dev = lambda a: torch.from_numpy(a.view(np.int16)).to(self.dev).view(torch.bfloat16)
+        Wfc_dev = to_dev(Wfc)
+        n_copies = max(2, -(-(1 << 30) // (Wfc.size * 2)))
+        return dict(kind="fusion", x=x, Wfc=Wfc, x_dev=to_dev(x), copies=[Wfc_dev] + [Wfc_dev.clone() for _ in range(n_copies - 1)],
+                    g=torch.empty((w["rows"], d), dtype=torch.bfloat16, device=self.dev), build_ms=0.0, n_copies=n_copies)
+
     def prepare(self, w):
         import numpy as np
         torch, vt, synth = self.torch, self.vt, self.synth
+        kind = w.get("kind", "head")
+        if kind == "fusion":
+            return self.prepare_fusion(w)
         Wh, Wd = self.full_W(w["H"])
         ids = synth.zipf_subset(0, synth.FULL_VOCAB, w["Vd"])
         ids_dev = torch.from_numpy(ids).to(self.dev)
         h = synth.gen_h(0, w["rows"], w["H"], peaked_frac=w["peaked"])
         h_dev = torch.from_numpy(h.view(np.int16)).to(self.dev).view(torch.bfloat16)
         # one-time set-up, timed on its own
-        W_sub, d2t = vt.vt_build_subset(Wd, ids_dev)
-        torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        vt.vt_build_subset(Wd, ids_dev, W_sub, d2t)
-        e1.record()
+        if kind == "head_q":
+            vt.vt_build_subset_q(Wd, ids_dev, w["fmt"])
+            torch.cuda.synchronize()
+            e0.record()
+            codes, scales, d2t = vt.vt_build_subset_q(Wd, ids_dev, w["fmt"])
+            e1.record()
+            first = (codes, scales)
+            nbytes = codes.numel() + scales.numel() * scales.element_size()
+        else:
+            W_sub, d2t = vt.vt_build_subset(Wd, ids_dev)
+            torch.cuda.synchronize()
+            e0.record()
+            vt.vt_build_subset(Wd, ids_dev, W_sub, d2t)
+            e1.record()
+            first = (W_sub,)
+            nbytes = W_sub.numel() * 2
         torch.cuda.synchronize()
         build_ms = e0.elapsed_time(e1)
-        nbytes = W_sub.numel() * 2
         n_copies = max(2, -(-(1 << 30) // nbytes))
-        copies = [W_sub] + [W_sub.clone() for _ in range(n_copies - 1)]
-        ws = vt.new_workspace(vt.vt_draft_head_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"]), self.dev)
+        copies = [first] + [tuple(t.clone() for t in first) for _ in range(n_copies - 1)]
+        ws = vt.new_workspace(vt.vt_draft_head_fused_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"]), self.dev)
         out_ids = torch.empty((w["rows"], w["k"]), dtype=torch.int32, device=self.dev)
         out_lp = torch.empty((w["rows"], w["k"]), dtype=torch.float32, device=self.dev)
-        return dict(ids=ids, h=h, h_dev=h_dev, d2t=d2t, copies=copies, ws=ws, out_ids=out_ids, out_lp=out_lp,
-                    build_ms=build_ms, n_copies=n_copies)
+        if self.operands == "zero_h":
+            h_dev.zero_()
+        elif self.operands == "const":
+            h_dev.fill_(1.0)
+            for c in copies:
+                c[0].fill_(0.0201 if kind != "head_q" else 57)
+        st = dict(kind=kind, ids=ids, h=h, h_dev=h_dev, d2t=d2t, copies=copies, ws=ws, out_ids=out_ids, out_lp=out_lp,
+                  build_ms=build_ms, n_copies=n_copies)
+        if kind == "head_fused":
+            gamma = synth.f32_to_bf16((1.0 + 0.1 * synth.normal(0, 9, 0, w["H"])).astype(np.float32))
+            parent = (-np.abs(synth.normal(0, 10, 0, w["rows"]))).astype(np.float32)
+            st.update(gamma=gamma, parent=parent, gamma_dev=torch.from_numpy(gamma.view(np.int16)).to(self.dev).view(torch.bfloat16),
+                      parent_dev=torch.from_numpy(parent).to(self.dev))
+        return st
 
     def time_mode(self, w, st, steps, warmup, cold, percall):
         """Dense-loop mean and per-call percentiles of one mode (cold: rotating W_sub copies)."""
@@ -147,8 +207,21 @@ class Runner:
         copies = st["copies"] if cold else st["copies"][:1]
         n = len(copies)
 
-        def step(i):
-            vt.vt_draft_head(st["h_dev"], copies[i % n], st["d2t"], w["k"], st["out_ids"], st["out_lp"], st["ws"])
+        kind = st["kind"]
+        if kind == "fusion":
+            def step(i):
+                vt.vt_feature_fusion(st["x_dev"], copies[i % n], st["g"])
+        elif kind == "head_q":
+            def step(i):
+                c = copies[i % n]
+                vt.vt_draft_head_q(st["h_dev"], c[0], c[1], w["fmt"], st["d2t"], w["k"], st["out_ids"], st["out_lp"], st["ws"])
+        elif kind == "head_fused":
+            def step(i):
+                vt.vt_draft_head_fused(st["h_dev"], st["gamma_dev"], 1e-5, copies[i % n][0], st["d2t"], w["k"], st["parent_dev"],
+                                       st["out_ids"], st["out_lp"], st["ws"])
+        else:
+            def step(i):
+                vt.vt_draft_head(st["h_dev"], copies[i % n][0], st["d2t"], w["k"], st["out_ids"], st["out_lp"], st["ws"])
 
         for i in range(warmup):
             step(i)
@@ -179,7 +252,7 @@ class Runner:
 
 def report(w, st, cold, warm):
     nbytes, flops = algorithmic(w)
-    regime = "hbm" if w["rows"] <= 16 else "mfma"
+    regime = "hbm" if (w["rows"] <= 16 or w.get("kind") == "fusion") else "mfma"   # the fusion layer at 64 rows is still 64 FLOP per byte
     t_s = cold["us_per_step"] * 1e-6   # dense-loop device time per step (wall clock if that is larger)
     gbs = nbytes / t_s / 1e9
     tfl = flops / t_s / 1e12
@@ -188,7 +261,9 @@ def report(w, st, cold, warm):
     else:
         roof = dict(bound="mfma", achieved=tfl, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
                     frac=tfl / MFMA_BF16_PEAK_TFLOPS, traffic=None)
-    roof["kernel"] = "streaming head kernel (whole step)" if regime == "hbm" else "gemm_head_kernel + merge_kernel (whole step)"
+    kind = w.get("kind", "head")
+    roof["kernel"] = ("feature-fusion kernel (whole call)" if kind == "fusion" else "streaming head kernel (whole step)" if regime == "hbm"
+                      else "gemm_head_kernel + merge_kernel (whole step)")
     roof["from"] = "cold dense-loop time per step"
     roof["algorithmic_bytes"] = nbytes
     roof["algorithmic_flops"] = flops
@@ -204,6 +279,19 @@ def report(w, st, cold, warm):
 def cpu_baseline(runner, w, st, budget_s):
     """The CPU oracle, as it stands, on a bounded sample of the workload's rows."""
     from oracle import vt_oracle as vo
+    kind = st["kind"]
+    if kind == "fusion":
+        from oracle import vp_oracle as vp
+        rows = st["x"].shape[0]
+        r_use = min(rows, 4)
+        reps, t_total = 0, 0.0
+        while t_total < budget_s and reps < 5000:
+            t0 = time.perf_counter()
+            vp.feature_fusion(st["x"][:r_use], st["Wfc"])
+            t_total += time.perf_counter() - t0
+            reps += 1
+        return dict(value=t_total / reps / r_use * 1e6 * rows, unit="us/step", cores=vo.num_threads(), kind="oracle",
+                    sample="%d of %d rows, %d repetitions, %.1f s of CPU time; scaled by rows" % (r_use, rows, reps, t_total))
     Wh, _ = runner.full_W(w["H"])
     ids = st["ids"]
     W_sub = Wh if len(ids) == Wh.shape[0] else Wh[ids]
@@ -211,9 +299,18 @@ def cpu_baseline(runner, w, st, budget_s):
     r_use = min(rows, 4)
     h = st["h"][:r_use]
     reps, t_total = 0, 0.0
+    if kind == "head_q":
+        from oracle import vq_oracle as vq
+        codes, scales = vq.quantize(W_sub, w["fmt"])        # set-up, not timed
+        call = lambda: vq.draft_head_q(h, codes, scales, w["fmt"], ids, w["k"], want_logits=False)
+    elif kind == "head_fused":
+        from oracle import vp_oracle as vp
+        call = lambda: vp.head_fused(h, st["gamma"], 1e-5, W_sub, ids, w["k"], st["parent"][:r_use])
+    else:
+        call = lambda: vo.draft_head(h, W_sub, ids, w["k"], want_logits=False)
     while t_total < budget_s and reps < 5000:
         t0 = time.perf_counter()
-        vo.draft_head(h, W_sub, ids, w["k"], want_logits=False)
+        call()
         t_total += time.perf_counter() - t0
         reps += 1
     per_row_us = t_total / reps / r_use * 1e6
@@ -332,6 +429,7 @@ def main():
         print(json.dumps({"selector": selector_bench(torch, vt, synth, dev, with_cpu=not args.no_cpu)}))
         return
     runner = Runner(torch, vt, synth, dev)
+    runner.operands = args.operands
 
     wl = workloads()
     if args.shape:
@@ -384,7 +482,8 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
-        "data": "synthetic (seeded N(0,0.02) W, N(0,1) h, Zipf(1.1)-ranked subsets); value = cold: rotating W_sub copies > 1 GiB",
+        "data": "synthetic (seeded N(0,0.02) W, N(0,1) h, Zipf(1.1)-ranked subsets); value = cold: rotating W_sub copies > 1 GiB"
+                + ("" if args.operands == "gaussian" else "; OPERAND ABLATION: %s" % args.operands),
         "config": {"workload": describe(head), "mode": "cold",
                    "percall_median_us": head_rep["cold"].get("percall_median_us"),
                    "percall_p10_us": head_rep["cold"].get("percall_p10_us"),

@@ -136,7 +136,9 @@ hipError_t launch_feature_fusion(const uint16_t* x, int rows, int d_in, const ui
     p.rows = rows;
     p.H = d_in;
     p.Vd = d_out;
-    p.tile = (rows > 128 && d_in % 64 == 0) ? 1 : 0;
+    // up to 128 rows: 32-feature tiles, so that d_out / 32 workgroups share the read of W_fc (128-feature tiles
+    // would leave most compute units idle: d_out = 4096 gives 32 of them)
+    p.tile = rows <= 128 ? 2 : (d_in % 64 == 0) ? 1 : 0;
     int BMV, BNR, ppv;
     gemm_tile_dims(p.tile, BMV, BNR, ppv);
     p.n_vtiles = (d_out + BMV - 1) / BMV;
@@ -153,6 +155,8 @@ hipError_t launch_feature_fusion(const uint16_t* x, int rows, int d_in, const ui
     ga.store_out = g_out;
     if (p.tile == 1)
         return launch_tile<2, 4, 4, 2, 1, false, true>(p, ga, s);
+    if (p.tile == 2)
+        return launch_tile<1, 4, 1, 1, 1, true, true>(p, ga, s);
     return launch_tile<2, 2, 2, 2, 1, true, true>(p, ga, s);
 }
 
