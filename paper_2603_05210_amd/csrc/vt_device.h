@@ -105,20 +105,23 @@ struct TopList {
 
 // ---- cross-lane exchange on the VALU (DPP / permlane swaps; no LDS round trip) ----
 // xchg<OFF>(x) returns the value held by lane (l ^ OFF).  Lane mappings used (checked on
-// gfx950): quad_perm for 1 and 2; row_shl:4 / row_shr:4 under complementary bank masks for 4;
+// gfx950): quad_perm for 1 and 2; quad reversal followed by row_half_mirror for 4;
 // row_ror:8 for 8; v_permlane16_swap / v_permlane32_swap for 16 and 32.
 template <int OFF>
 __device__ __forceinline__ int xchg_i(int x, int lane)
 {
+    // (every lane has a source lane for distances 1, 2 and 8, so the plain DPP move serves: no
+    // copy of the old value is needed)
     if constexpr (OFF == 1) {
-        return __builtin_amdgcn_update_dpp(x, x, 0xB1, 0xf, 0xf, false);
+        return __builtin_amdgcn_mov_dpp(x, 0xB1, 0xf, 0xf, true);
     } else if constexpr (OFF == 2) {
-        return __builtin_amdgcn_update_dpp(x, x, 0x4E, 0xf, 0xf, false);
+        return __builtin_amdgcn_mov_dpp(x, 0x4E, 0xf, 0xf, true);
     } else if constexpr (OFF == 4) {
-        int t = __builtin_amdgcn_update_dpp(x, x, 0x104, 0xf, 0x5, false);
-        return __builtin_amdgcn_update_dpp(t, x, 0x114, 0xf, 0xa, false);
+        // l ^ 4 = (l ^ 3) ^ 7: reverse the quads, then mirror each half row of eight
+        const int t = __builtin_amdgcn_mov_dpp(x, 0x1B, 0xf, 0xf, true);
+        return __builtin_amdgcn_mov_dpp(t, 0x141, 0xf, 0xf, true);
     } else if constexpr (OFF == 8) {
-        return __builtin_amdgcn_update_dpp(x, x, 0x128, 0xf, 0xf, false);
+        return __builtin_amdgcn_mov_dpp(x, 0x128, 0xf, 0xf, true);
     } else if constexpr (OFF == 16) {
         const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
         return (lane & 16) ? (int)r[0] : (int)r[1];
