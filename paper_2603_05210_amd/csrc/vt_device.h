@@ -433,6 +433,19 @@ __device__ __forceinline__ k64 k64_merge_16_lists(const k64* lists, int lane)
     return m;
 }
 
+// Largest key of the wave, in every lane.
+__device__ __forceinline__ k64 k64_wave_max(k64 c, int lane)
+{
+    k64 p;
+    p = k64_xchg<1>(c, lane), c = p > c ? p : c;
+    p = k64_xchg<2>(c, lane), c = p > c ? p : c;
+    p = k64_xchg<4>(c, lane), c = p > c ? p : c;
+    p = k64_xchg<8>(c, lane), c = p > c ? p : c;
+    p = k64_xchg<16>(c, lane), c = p > c ? p : c;
+    p = k64_xchg<32>(c, lane), c = p > c ? p : c;
+    return c;
+}
+
 // Sorts the 16 keys of every 16-lane row best first (bitonic sorting network, ten stages).
 template <int S, int OFF>
 __device__ __forceinline__ k64 k64_sort_stage(k64 c, int lane)

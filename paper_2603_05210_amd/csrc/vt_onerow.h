@@ -56,6 +56,18 @@ __device__ __forceinline__ void coherent_load_issue(float2& dst, const float2* p
 {
     asm volatile("global_load_dwordx2 %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
 }
+__device__ __forceinline__ void coherent_load_issue(float& dst, const float* p)
+{
+    asm volatile("global_load_dword %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void coherent_load_issue(int& dst, const int* p)
+{
+    asm volatile("global_load_dword %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void coherent_load_wait(float& a, int& b, float2& c)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
+}
 __device__ __forceinline__ void coherent_load_wait(f32x4& a, i32x4& b, float2& c)
 {
     asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c) : : "memory");
@@ -289,8 +301,10 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
 
     // ---- wave 0 merges the 16 lists; waves 1..15 sum the softmax statistics over fixed slices ----
     k64 best = 0;
+    const bool single = a.k == 1;  // one candidate per list: plain maxima instead of the merge networks
     if (wave == 0) {
-        best = k64_merge_16_lists(wl, lane);
+        best = single ? k64_wave_max(lane < kGemvWaves ? wl[lane * 16] : k64_make(kKeyNone, kIdxNone), lane)
+                      : k64_merge_16_lists(wl, lane);
     } else {
         const int per = (n_wg + 14) / 15;  // at most 69 logits per slice: two per lane
         const int lo = (wave - 1) * per;
@@ -352,6 +366,46 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
     k64* wl2 = reinterpret_cast<k64*>(lds + kLdsWl2);
     float2* fst = reinterpret_cast<float2*>(lds + kLdsFst);
     const int P = gridDim.x;
+    if (single) {
+        // k = 1: the head of every workgroup's list and its statistics, one workgroup per thread
+        float v = neg_inf();
+        int ix = kIdxNone;
+        float2 st = make_float2(neg_inf(), 0.0f);
+        const bool okp = tid < P;
+        if (okp) {
+            coherent_load_issue(v, a.part_val + 16 * tid);
+            coherent_load_issue(ix, a.part_idx + 16 * tid);
+            coherent_load_issue(st, a.part_stat + tid);
+        }
+        coherent_load_wait(v, ix, st);
+        float m = st.x, s = st.y;
+        if (wave < 4) {
+            const k64 top = k64_wave_max(k64_make(f2key(v), ix), lane);
+            wave_stat_merge(m, s, okp);
+            if (lane == 0) {
+                wl2[wave] = top;
+                fst[wave] = make_float2(m, s);
+            }
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const k64 fin = k64_wave_max(lane < 4 ? wl2[lane] : k64_make(kKeyNone, kIdxNone), lane);
+            const bool act = lane < 4;
+            float mv = act ? fst[act ? lane : 0].x : neg_inf();
+            float sv = act ? fst[act ? lane : 0].y : 0.0f;
+            wave_stat_merge(mv, sv, act);
+            const float lse = mv + __logf(sv);
+            if (lane == 0) {
+                const int oi = k64_idx(fin);
+                a.out_ids[0] = (oi != kIdxNone) ? a.d2t[oi] : -1;
+                a.out_logp[0] = (key2f(k64_key(fin)) - lse) + (a.parent != nullptr ? a.parent[0] : 0.0f);
+                if (a.lse_out != nullptr)
+                    a.lse_out[0] = lse;
+                __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        return;
+    }
     {
         // all lists into LDS as keys: thread t takes entries 4t .. 4t+3 with two 128-bit device-coherent
         // loads, and one workgroup's statistics; every load is in flight before the first is awaited
