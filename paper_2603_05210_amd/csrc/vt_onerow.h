@@ -44,6 +44,7 @@ __device__ __forceinline__ int row_shr1(int x, int fill)
 // destinations as operands, so no use can be scheduled ahead of it.
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ void coherent_load_issue(f32x4& dst, const float* p)
 {
     asm volatile("global_load_dwordx4 %0, %1, off sc1" : "=&v"(dst) : "v"(p) : "memory");
@@ -84,6 +85,7 @@ constexpr int kLdsWl2 = kLdsCand + 256 * 16 * 8;                // k64[16][16]  
 constexpr int kLdsFst = kLdsWl2 + 16 * 16 * 8;                  // float2[16]
 constexpr int kLdsTotal = kLdsFst + 16 * 8;
 constexpr int kLdsH = kLdsCand;  // u32x4[512]: the hidden state on its way to the waves' registers (dead before the final merge)
+constexpr int kLdsPs = kLdsCand + 8192;  // uint8[16][512]: per wave, the block exponents of its hand-out (dead before the final merge)
 
 
 // ---- storage formats of W_sub ----
@@ -138,10 +140,19 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
 
     const u32x4* wp = a.W + (size_t)j0 * nchunk + lane;
     auto slot_ptr = [&](int grp, int i) { return wp + (size_t)(grp * G + i / T) * nchunk + (i % T) * kWave; };
-    // scales: one fp32 per row (kRowScale) or one exponent byte per piece and lane (kPieceScale)
+    // scales: one fp32 per row (kRowScale) or one exponent byte per piece (kPieceScale).  The bytes of a
+    // hand-out are contiguous (D * 64 of them): the wave fetches them with one 8-byte load per lane and
+    // passes them through its own 512 bytes of LDS, where lane l picks up byte i * 64 + l for piece i.
     const float* rsp = reinterpret_cast<const float*>(a.scales) + j0;
-    const uint8_t* psp = reinterpret_cast<const uint8_t*>(a.scales) + (size_t)j0 * nchunk + lane;
-    auto pscale_ptr = [&](int grp, int i) { return psp + (size_t)(grp * G + i / T) * nchunk + (i % T) * kWave; };
+    constexpr int kPsBytes = D * kWave;
+    const uint8_t* psg = reinterpret_cast<const uint8_t*>(a.scales) + (size_t)j0 * nchunk;
+    uint8_t* psl = reinterpret_cast<uint8_t*>(lds + kLdsPs) + wave * kPsBytes;
+    auto load_ps = [&](int grp, bool full) {
+        u32x2 v = {0x7f7f7f7fu, 0x7f7f7f7fu};
+        if (full || grp * G + (8 * lane) / nchunk < n_wg)  // rows past the workgroup's run are not read
+            v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(psg + (size_t)grp * kPsBytes) + lane);
+        return v;
+    };
 
     // the hidden state: one 8-byte piece (four bf16) per thread, requested before anything else
     const int hpiece = tid < H / 4 ? tid : H / 4 - 1;
@@ -156,7 +167,13 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
         s_next = kGemvWaves;
     int gc = wave;
     u32x4 buf[D];
-    uint32_t sbuf[F::kPieceScale ? D : 1];  // exponent bytes of the pieces in flight
+    uint32_t sbuf[F::kPieceScale ? D : 1];  // exponent bytes of the current hand-out's pieces
+    auto put_ps = [&](const u32x2& v) {
+        reinterpret_cast<u32x2*>(psl)[lane] = v;  // LDS operations of one wave complete in order
+#pragma unroll
+        for (int i = 0; i < D; ++i)
+            sbuf[i] = psl[i * kWave + lane];
+    };
     float rsbuf[F::kRowScale ? G : 1];      // row scales of the rows in flight
     // The first pieces of W_sub are requested, then h goes through LDS to every wave.  When the
     // wave's first hand-out is full its loads are unconditional, so the compiler knows how many
@@ -207,26 +224,34 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
     };
     auto load_slot = [&](int grp, int i) {
         buf[i] = __builtin_nontemporal_load(slot_ptr(grp, i));
-        if constexpr (F::kPieceScale)
-            sbuf[i] = __builtin_nontemporal_load(pscale_ptr(grp, i));
         if constexpr (F::kRowScale) {
             if (i % T == 0)
                 rsbuf[i / T] = __builtin_nontemporal_load(rsp + grp * G + i / T);
         }
     };
     if (gc < nfull) {
+        u32x2 ps0 = {0u, 0u};
+        if constexpr (F::kPieceScale)
+            ps0 = load_ps(gc, true);
 #pragma unroll
         for (int i = 0; i < D; ++i)
             load_slot(gc, i);
         stage_h();
+        if constexpr (F::kPieceScale)
+            put_ps(ps0);
         asm volatile("; first hand-out full");  // keeps the two copies apart (exact load count in this one)
     } else {
+        u32x2 ps0 = {0u, 0u};
+        if constexpr (F::kPieceScale)
+            ps0 = load_ps(gc, false);
 #pragma unroll
         for (int i = 0; i < D; ++i) {
             if (gc * G + i / T < n_wg)
                 load_slot(gc, i);
         }
         stage_h();
+        if constexpr (F::kPieceScale)
+            put_ps(ps0);
         asm volatile("; first hand-out partial or none");
     }
     auto grab = [&]() {
@@ -247,6 +272,9 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
     auto iteration = [&](auto steady_c) {
         constexpr bool STEADY = decltype(steady_c)::value;
         const unsigned int gnn_raw = grab();  // the hand-out after next: its LDS round trip hides under this iteration
+        u32x2 psn = {0u, 0u};
+        if constexpr (F::kPieceScale)
+            psn = load_ps(gn, STEADY);
 #pragma unroll
         for (int i = 0; i < D; ++i) {
             const int rr = gc * G + i / T;  // row within the workgroup's run
@@ -284,6 +312,8 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_one_row_kernel(GemvArgs a)
             if (STEADY)
                 __builtin_amdgcn_sched_barrier(0);  // keep "consume piece i, request its successor" in this order
         }
+        if constexpr (F::kPieceScale)
+            put_ps(psn);  // the next hand-out's exponents: they arrived before its first piece
         gc = gn;
         gn = (int)__builtin_amdgcn_readfirstlane(gnn_raw);
     };
