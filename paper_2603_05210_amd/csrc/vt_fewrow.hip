@@ -1,0 +1,362 @@
+// The draft step for a few hidden states at once (2..16 rows: the nodes one tree-drafting step
+// expands for one sequence, or a small batch): Section 2.3's projection, bound by reading W_sub
+// once whatever the row count, with the log-softmax statistics, the k best per row and the d2t
+// remap in the same launch.
+//
+//   - a workgroup owns a contiguous run of W_sub rows and walks it 16 rows (one MFMA block) at a
+//     time; its 16 waves cut the hidden dimension between them: wave w multiplies columns
+//     [w * H/16, (w+1) * H/16) of every block, so the hidden states it needs (B operands of
+//     v_mfma_f32_16x16x32_bf16, columns beyond `rows` zero) stay in its registers for the whole
+//     call and no hidden state passes through LDS;
+//   - global loads stay line-sized (an instruction takes 128 contiguous bytes of each of 8 rows);
+//     a wave-private LDS buffer turns them into A fragments (lane l: row l % 16, eight columns
+//     number l / 16 of a 32-column step).  Eight 1 KiB loads per wave are in flight at all times:
+//     the pieces of the next blocks are requested as the current ones are handed to LDS;
+//   - after a block's multiplications every wave leaves its 16 x 16 partial sums in LDS, one bare
+//     barrier (the loads in flight are not drained), and wave r < rows adds up, in a fixed order,
+//     the 16 partials of hidden state r: lane c ends with the logit of block row c.  Wave r keeps
+//     state r's softmax statistics (lane c over the block rows c) and its running list of the 16
+//     best (lane q of a 16-lane row holds the q-th best); a block row enters the list only if it
+//     beats the list's k-th entry -- rare once the list has warmed up -- by one shifted copy and
+//     two compares.  Which wave and lane see which W_sub row is fixed by the row's number, so the
+//     result does not depend on timing;
+//   - lists travel as 64-bit order keys (logit key, then lower draft index) and are merged by the
+//     bitonic network, one wave per hidden state: the lists of each group of 16 workgroups by the
+//     last of the group to arrive, then the groups' lists by the last group to finish, which
+//     emits ids (through d2t) and log-probabilities.
+#include <atomic>
+
+#include "vt_onerow.h"
+
+namespace vt {
+
+constexpr int kFewSlots = 8;                // 1 KiB load instructions in flight per wave
+constexpr int kFewStageBytes = 2 * 2048;    // per wave: two staging areas of 16 rows x 128 bytes
+// LDS map (bytes): staging areas, then two planes of partial sums for each of the NB blocks of an
+// iteration (per wave 64 lanes x 16 bytes, one spare piece per 16 lanes); once the stream has ended
+// the merge stages' candidates (k64[16 states][256]) overlay the staging areas.
+constexpr int kFewLdsStage = 0;
+constexpr int kFewLdsPart = kGemvWaves * kFewStageBytes;  // 64 KiB
+constexpr int kFewPlaneBytes = 64 * 16 + 5 * 16;  // an odd number of 16-byte pieces: the four quarters of a read fall on two bank groups
+constexpr int kFewLdsWl = 0;
+constexpr int few_lds_bytes(int nb) { return kFewLdsPart + 2 * nb * kGemvWaves * kFewPlaneBytes; }
+
+// KS: 32-column steps a wave multiplies per W_sub row (H = 512 * KS).
+template <int KS>
+__global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
+{
+    constexpr int D = kFewSlots;
+    constexpr int NB = D / KS;          // 16-row blocks per loop iteration
+    constexpr int nchunk = 64 * KS;     // 16-byte pieces per W_sub row
+    static_assert(KS == 4 || KS == 8, "whole 128-byte lines per wave and row, whole blocks per iteration");
+    extern __shared__ u32x4 smem[];
+    __shared__ int s_flag;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int m16 = lane & 15;  // MFMA: row of the A fragment / hidden state of the B fragment and of the result
+    const int g4 = lane >> 4;   // MFMA: which eight columns of a 32-column step; the result's rows 4 * g4 ..+3
+    char* lds = reinterpret_cast<char*>(smem);
+
+    // rows of this workgroup: an even split of V_draft over the grid, in order
+    const int nb = gridDim.x;
+    const int b = blockIdx.x;
+    const int base = a.Vd / nb;
+    const int rem = a.Vd - base * nb;
+    const int n_wg = base + (b < rem ? 1 : 0);
+    const int j0 = b * base + (b < rem ? b : rem);
+    const int nblk = (n_wg + 15) >> 4;
+    const int niter = (nblk + NB - 1) / NB;
+
+    // Both operands are fetched line-sized: an instruction takes 128 contiguous bytes of each of 8 rows;
+    // lane l takes piece (l % 8) ^ f(row) of row l / 8 (+8 for odd instructions) and parks it at
+    // position l of a wave-private staging area, so that the fragment read of piece c of row i is at
+    // i * 8 + (c ^ f(i)) with f(i) = (i / 2) % 8: no bank conflicts on either side.
+    const int ld_row = lane >> 3;
+    const int pc_a = (lane & 7) ^ ((ld_row >> 1) & 7);
+    const int pc_b = (lane & 7) ^ (((ld_row + 8) >> 1) & 7);
+
+    // B operands: the wave's columns of every hidden state, requested before anything else (hidden
+    // states beyond `rows` repeat state 0 and are zeroed once they are fragments)
+    u32x4 hreg[KS];
+#pragma unroll
+    for (int d = 0; d < KS; ++d) {
+        const int r = ld_row + ((d & 1) ? 8 : 0);
+        hreg[d] = a.h[(size_t)(r < a.rows ? r : 0) * nchunk + wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
+    }
+
+    // A operands.  Slot d of an iteration: block d / KS, 128-byte line (d % KS) / 2 of the wave's
+    // columns, rows 0..7 (even d) or 8..15 (odd d) of the block.  Rows past the workgroup's run
+    // repeat its last row (their results are dropped).
+    const u32x4* wbase = a.W + (size_t)j0 * nchunk + wave * (KS * 4);
+    u32x4 buf[D];
+    auto issue = [&](int it, int d) {
+        const int blk = it * NB + d / KS;
+        int r = blk * 16 + ld_row + ((d & 1) ? 8 : 0);
+        r = r < n_wg ? r : n_wg - 1;
+        const int piece = ((d % KS) >> 1) * 8 + ((d & 1) ? pc_b : pc_a);
+        buf[d] = __builtin_nontemporal_load(wbase + (size_t)r * nchunk + piece);
+    };
+#pragma unroll
+    for (int d = 0; d < D; ++d) {
+        issue(0, d);
+        __builtin_amdgcn_sched_barrier(0);  // in slot order, as every later iteration requests them
+    }
+
+    u32x4* stage = reinterpret_cast<u32x4*>(lds + kFewLdsStage + wave * kFewStageBytes);
+    float* part = reinterpret_cast<float*>(lds + kFewLdsPart);
+    const int a_sw = (m16 >> 1) & 7;
+    // the hidden states become fragments while the first W_sub pieces are on their way
+#pragma unroll
+    for (int c = 0; c < KS / 2; ++c) {
+        u32x4* st = stage + (c & 1) * 128;
+        st[lane] = hreg[2 * c];
+        st[kWave + lane] = hreg[2 * c + 1];
+        __builtin_amdgcn_wave_barrier();
+        const u32x4 x0 = st[m16 * 8 + (g4 ^ a_sw)];
+        const u32x4 x1 = st[m16 * 8 + ((4 + g4) ^ a_sw)];
+        __builtin_amdgcn_wave_barrier();
+        hreg[2 * c] = m16 < a.rows ? x0 : u32x4{0u, 0u, 0u, 0u};
+        hreg[2 * c + 1] = m16 < a.rows ? x1 : u32x4{0u, 0u, 0u, 0u};
+    }
+
+    // wave r < rows keeps hidden state r's results: the running list of its 16 best (lane q of every
+    // 16-lane row holds the q-th best) and, in lane c, the running maximum and sum of exponentials
+    // over the block rows c it has seen
+    const int rows = a.rows;
+    const bool mine = wave < rows;
+    const int kth = a.k - 1;
+    int lkey = kKeyNone, lidx = kIdxNone;
+    int thr = kKeyNone;  // key of the list's k-th entry: a logit that does not beat it cannot be among the k best
+    float rm = neg_inf(), rs = 0.0f;
+    f32x4 acc[NB];
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+        acc[i] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    // where the partial sums of (wave p, block bi) of a plane sit, and lane l's 16 bytes in them
+    // (one spare piece per 16 lanes spreads the reads below over all banks)
+    auto part_at = [&](int buf_i, int bi, int p, int l) {
+        return part + ((buf_i * NB + bi) * kGemvWaves + p) * (kFewPlaneBytes / 4) + l * 4 + (l >> 4) * 4;
+    };
+
+    auto iteration = [&](int it, auto more_c) {
+        constexpr bool MORE = decltype(more_c)::value;  // another iteration follows: its loads are unconditional
+#pragma unroll
+        for (int c = 0; c < D / 2; ++c) {
+            u32x4* st = stage + (c & 1) * 128;
+            st[lane] = buf[2 * c];
+            st[kWave + lane] = buf[2 * c + 1];
+            if (MORE) {
+                issue(it + 1, 2 * c);
+                issue(it + 1, 2 * c + 1);
+            }
+            __builtin_amdgcn_wave_barrier();  // the wave's LDS accesses stay in program order
+            const u32x4 w0 = st[m16 * 8 + (g4 ^ a_sw)];
+            const u32x4 w1 = st[m16 * 8 + ((4 + g4) ^ a_sw)];
+            __builtin_amdgcn_wave_barrier();
+            const int bi = (2 * c) / KS;
+            const int i0 = (2 * c) % KS;
+            acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w0),
+                                                             __builtin_bit_cast(bf16x8, hreg[i0]), acc[bi], 0, 0, 0);
+            acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w1),
+                                                             __builtin_bit_cast(bf16x8, hreg[i0 + 1]), acc[bi], 0, 0, 0);
+        }
+        // the wave's partial sums of the iteration's blocks go to plane it % 2: lane (state m16, g4)
+        // holds block rows 4 g4 .. 4 g4 + 3 of that state
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+            *reinterpret_cast<f32x4*>(part_at(it & 1, bi, wave, lane)) = acc[bi];
+            acc[bi] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only: the loads in flight stay in flight
+        __builtin_amdgcn_s_barrier();
+        if (!mine)
+            return;
+        // state `wave`: lane (c = m16, q = g4) adds the partials of waves 4 q .. 4 q + 3 for block row c,
+        // two exchanges add the four quarters: every lane c ends with the logit of block row c
+#pragma unroll
+        for (int bi = 0; bi < NB; ++bi) {
+            const int src = (m16 >> 2) * 16 + wave;  // the lane that held (state `wave`, block rows 4 (c / 4) ..)
+            const float x0 = part_at(it & 1, bi, 4 * g4 + 0, src)[m16 & 3];
+            const float x1 = part_at(it & 1, bi, 4 * g4 + 1, src)[m16 & 3];
+            const float x2 = part_at(it & 1, bi, 4 * g4 + 2, src)[m16 & 3];
+            const float x3 = part_at(it & 1, bi, 4 * g4 + 3, src)[m16 & 3];
+            float z = (x0 + x1) + (x2 + x3);
+            z += xchg_f<16>(z, lane);
+            z += xchg_f<32>(z, lane);
+            const int jb = (it * NB + bi) * 16;  // the block's first row within the workgroup's run
+            const bool valid = jb + m16 < n_wg;
+            const int zk = valid ? f2key(z) : kKeyNone;
+            if (valid) {
+                // one exponential per logit: the smaller of (running maximum, logit) is rescaled
+                const float d = z - rm;
+                const float e = __expf(-fabsf(d));
+                rs = d > 0.0f ? rs * e + 1.0f : rs + e;
+                rm = fmaxf(rm, z);
+                if (a.logits_out != nullptr && g4 == 0)
+                    a.logits_out[(size_t)wave * a.Vd + j0 + jb + m16] = z;
+            }
+            // block rows that beat the list's k-th entry enter the list one by one, in row order
+            // (ties keep the earlier, lower index ahead)
+            unsigned int todo = (unsigned int)__builtin_amdgcn_ballot_w64(zk > thr) & 0xffffu;
+            while (todo != 0u) {
+                const int c = __builtin_ctz(todo);
+                todo &= todo - 1u;
+                const int zs = __builtin_amdgcn_readlane(zk, c);
+                if (zs > thr) {
+                    const int sk = row_shr1(lkey, kKeyMax);
+                    const int si = row_shr1(lidx, kIdxNone);
+                    const bool c0 = zs > lkey;
+                    const bool c1 = zs > sk;
+                    lkey = c0 ? (c1 ? sk : zs) : lkey;
+                    lidx = c0 ? (c1 ? si : j0 + jb + c) : lidx;
+                    thr = __builtin_amdgcn_readlane(lkey, kth);
+                }
+            }
+        }
+    };
+    // (a loop of the steady form alone, the last iteration on its own: the compiler then knows the
+    // number of loads in flight at every wait)
+    for (int it = 0; it + 1 < niter; ++it)
+        iteration(it, std::true_type{});
+    iteration(niter - 1, std::false_type{});
+    __syncthreads();  // staging areas and partial planes are dead from here on
+
+    // ---- the workgroup's result for state `wave` is the wave's own list and statistics ----
+    k64* cand = reinterpret_cast<k64*>(lds + kFewLdsWl) + wave * 256;  // the wave's own 2 KiB (fetched lists)
+    k64 best = k64_make(lkey, lidx);
+    float mm = rm, ss = rs;
+    if (mine)
+        wave_stat_merge(mm, ss, lane < 16);
+    // a result list goes to slot `slot` of the workspace: [slot][state] lists of 16 and one (max, sum) pair
+    auto publish = [&](int slot) {
+        if (mine) {
+            const size_t at = (size_t)slot * rows + wave;
+            if (lane < 16) {
+                st_dev(a.part_val + at * 16 + lane, key2f(k64_key(best)));
+                st_dev(a.part_idx + at * 16 + lane, k64_idx(best));
+            }
+            if (lane == 0) {
+                st_dev(reinterpret_cast<float*>(a.part_stat + at), mm);
+                st_dev(reinterpret_cast<float*>(a.part_stat + at) + 1, ss);
+            }
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the coherent stores are acknowledged
+        __syncthreads();
+    };
+    // the lists of slots first .. first + count - 1 (count <= 16), merged per hidden state
+    auto merge_slots = [&](int first, int count) {
+        if (!mine)
+            return;
+        f32x4 v = {neg_inf(), neg_inf(), neg_inf(), neg_inf()};
+        i32x4 ix = {kIdxNone, kIdxNone, kIdxNone, kIdxNone};
+        float2 st = make_float2(neg_inf(), 0.0f);
+        const int li = lane >> 2;  // lane l: entries 4 * (l % 4) ..+3 of list l / 4
+        if (li < count) {
+            const size_t at = ((size_t)(first + li) * rows + wave) * 16 + 4 * (lane & 3);
+            coherent_load_issue(v, a.part_val + at);
+            coherent_load_issue(ix, a.part_idx + at);
+        }
+        const bool act = lane < count;
+        if (act)
+            coherent_load_issue(st, a.part_stat + (size_t)(first + lane) * rows + wave);
+        coherent_load_wait(v, ix, st);
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            cand[4 * lane + q] = k64_make(f2key(v[q]), ix[q]);
+        __builtin_amdgcn_wave_barrier();
+        best = k64_merge_16_lists(cand, lane);
+        mm = st.x;
+        ss = st.y;
+        wave_stat_merge(mm, ss, act);
+    };
+    auto emit = [&]() {
+        if (!mine)
+            return;
+        const float lse = mm + __logf(ss);
+        if (lane < a.k) {
+            const int oi = k64_idx(best);
+            a.out_ids[(size_t)wave * a.k + lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
+            a.out_logp[(size_t)wave * a.k + lane] =
+                (key2f(k64_key(best)) - lse) + (a.parent != nullptr ? a.parent[wave] : 0.0f);
+        }
+        if (lane == 0 && a.lse_out != nullptr)
+            a.lse_out[wave] = lse;
+    };
+
+    const int P = gridDim.x;
+    const int grp = blockIdx.x >> 4;
+    const int ngrp = (P + 15) >> 4;
+    const int in_grp = (grp == ngrp - 1) ? P - grp * 16 : 16;
+    if (P == 1) {  // nothing to wait for
+        emit();
+        return;
+    }
+    publish(blockIdx.x);
+    if (tid == 0) {
+        unsigned int* ctr = a.arrive + (1 + grp) * kArriveStrideWords;
+        const unsigned int t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = ((int)t == in_grp - 1) ? 1 : 0;
+        if (last)
+            __hip_atomic_store(ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_flag = last;
+    }
+    __syncthreads();
+    if (!s_flag)
+        return;
+    // ---- the last workgroup of its group of 16 merges the group's lists ----
+    merge_slots(grp * 16, in_grp);
+    if (ngrp == 1) {
+        emit();
+        return;
+    }
+    publish(P + grp);  // (every thread has read s_flag before this barrier)
+    if (tid == 0) {
+        const unsigned int t = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int last = ((int)t == ngrp - 1) ? 1 : 0;
+        if (last)
+            __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        s_flag = last;
+    }
+    __syncthreads();
+    if (!s_flag)
+        return;
+    // ---- the last group to finish merges the groups' lists and ends the call ----
+    merge_slots(P, ngrp);
+    emit();
+}
+
+// What the kernel assumes of a launch: 2..16 hidden states, lists of 16, at most 256 workgroups
+// (16 groups of 16) with their own and their groups' result slots in the workspace.
+static bool few_rows_launch_ok(const Plan& p, const GemvArgs& ga)
+{
+    return p.few_rows && ga.rows >= 2 && ga.rows <= 16 && ga.KP == 16 && ga.k <= 16 && p.blocks >= 1 && p.blocks <= 256 &&
+           ga.P == p.blocks + 16 && ga.fused && (p.H == 2048 || p.H == 4096) && ga.nchunk == p.H / 8;
+}
+
+template <int KS>
+static hipError_t launch_few_t(const Plan& p, const GemvArgs& ga, hipStream_t s)
+{
+    constexpr int lds = few_lds_bytes(kFewSlots / KS);
+    static_assert(lds <= kGemvLdsLimit, "fits a compute unit's LDS");
+    static std::atomic<int> raised{0};  // the dynamic LDS limit of this instantiation is raised once
+    if (!raised.load()) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_few_rows_kernel<KS>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+        if (e != hipSuccess)
+            return e;
+        raised.store(1);
+    }
+    hipLaunchKernelGGL((gemv_few_rows_kernel<KS>), dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
+    return hipGetLastError();
+}
+
+hipError_t launch_gemv_few_rows(const Plan& p, const GemvArgs& ga, hipStream_t s)
+{
+    if (!few_rows_launch_ok(p, ga))
+        return hipErrorInvalidValue;
+    return p.H == 4096 ? launch_few_t<8>(p, ga, s) : launch_few_t<4>(p, ga, s);
+}
+
+}  // namespace vt

@@ -482,6 +482,8 @@ hipError_t launch_gemv(const Plan& p, const HeadArgs& a, hipStream_t s)
     fill_gemv_args(p, a, ga);
     if (p.one_row)
         return launch_gemv_one_row(p, ga, s);
+    if (p.few_rows)
+        return launch_gemv_few_rows(p, ga, s);
     if (p.mfma)
         return launch_mfma(p, ga, s);
     // rows of W_sub a wave reduces together (J): measured best 1 for a single hidden row, 2 otherwise

@@ -90,6 +90,20 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         p.P = p.blocks;
         p.fused = 1;
         p.ks = 1;
+    } else if (rows >= 2 && rows <= kGemvMaxRows && p.KP <= 16 && (H == 2048 || H == 4096)) {
+        // 16 waves share each block of 16 W_sub rows, at most one workgroup per compute unit; the
+        // workspace holds a result slot per workgroup and one per group of 16 workgroups
+        p.regime = 0;
+        p.few_rows = 1;
+        p.KP = 16;
+        p.NR = 16;
+        p.J = 1;
+        p.rpb = 0;
+        int blocks = (int)((Vd + 15) / 16);
+        p.blocks = blocks > kGemvTargetBlocks ? kGemvTargetBlocks : blocks;
+        p.P = p.blocks + 16;
+        p.fused = 1;
+        p.ks = 1;
     } else if (streaming) {
         p.regime = 0;
         p.blocks = (int)((Vd + p.rpb - 1) / p.rpb);

@@ -36,6 +36,7 @@ struct Plan {
     int J;       // W_sub rows a wave reduces together
     int rpb;     // W_sub rows per workgroup
     int one_row; // the dedicated one-row kernel (H = 512, 1024, 2048 or 4096, lists of at most 16)
+    int few_rows; // the dedicated kernel for 2..16 rows (H = 2048 or 4096, lists of at most 16)
     int fused;   // the streaming kernel's last workgroup also does the final merge
     int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
     int ks;      // its slices of the hidden dimension per 16-row group (narrow ranges: keeps 16 waves busy)

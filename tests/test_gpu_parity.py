@@ -146,6 +146,58 @@ def test_exact_arithmetic_matrix_core_streaming(rows):
     assert np.max(np.abs(g_lp - ora.logp)) < 1e-3
 
 
+# The kernel for 2..16 rows at H = 2048 / 4096 (16 waves share every block of 16 W_sub rows; results
+# travel workgroup -> group of 16 workgroups -> call): one workgroup, one group, a last group of one
+# workgroup, ragged last blocks, every row-count set, k from 1 to 16.
+FEW_ROWS = [
+    (5, 4096, 500, 16, 16),      # a single workgroup with a single full block, k == V_draft
+    (3, 2048, 300, 17, 5),       # two workgroups of 9 and 8 rows
+    (2, 4096, 6000, 4096, 10),   # 256 workgroups of exactly one block
+    (13, 4096, 3000, 257, 1),    # 17 workgroups: the second group has one member
+    (10, 2048, 9000, 4380, 8),
+    (8, 4096, 20000, 13264, 10),
+    (16, 2048, 5000, 4097, 16),
+    (16, 4096, 9000, 8200, 16),  # 32 or 33 rows per workgroup: a ragged third block
+    (4, 2048, 70000, 66001, 10),
+]
+
+
+@pytest.mark.parametrize("rows,H,V,Vd,k", FEW_ROWS)
+def test_few_rows_kernel_full_comparison(rows, H, V, Vd, k):
+    _say("few rows: rows=%d H=%d V=%d Vd=%d k=%d" % (rows, H, V, Vd, k))
+    seed = rows * 977 + k
+    W = synth.gen_W(seed, V, H, std=0.05)
+    h = synth.gen_h(seed, rows, H, peaked_frac=0.1 if rows >= 10 else 0.0)
+    ids = synth.zipf_subset(seed, V, Vd)
+    Wsub_dev, d2t_dev, Wsub_o, d2t_o = build_both(W, ids)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, k)
+    ora = vo.draft_head(h, Wsub_o, d2t_o, k)
+    st = check_head(g_ids, g_lp, ora, d2t_o, gpu_logits=g_z, gpu_lse=g_lse)
+    _say("  %s" % st)
+    # the timed entry point, three times over one workspace (every counter must be back at zero)
+    ws = vt.new_workspace(vt.vt_draft_head_workspace_bytes(rows, H, Vd, k), DEV)
+    h_dev = to_dev_bf16(h)
+    for _ in range(3):
+        n_ids, n_lp = vt.vt_draft_head(h_dev, Wsub_dev, d2t_dev, k, workspace=ws)
+        torch.cuda.synchronize()
+        assert np.array_equal(n_ids.cpu().numpy(), g_ids) and np.array_equal(n_lp.cpu().numpy(), g_lp)
+
+
+@pytest.mark.parametrize("rows,H", [(2, 4096), (7, 2048), (12, 4096), (16, 2048)])
+def test_exact_arithmetic_few_rows_kernel(rows, H):
+    """Small-integer inputs through the kernel for 2..16 rows: logits bit for bit, ties (many) by draft index."""
+    Vd, k = 5001, 12
+    _say("exact (few rows) rows=%d H=%d" % (rows, H))
+    Wb = synth.small_int_bf16(7, 0, (Vd, H), lo=-2, hi=2)
+    hb = synth.small_int_bf16(7, 1, (rows, H), lo=-2, hi=2)
+    d2t = np.arange(Vd, dtype=np.int32)[::-1].copy()
+    g_ids, g_lp, g_z, g_lse = run_gpu(hb, to_dev_bf16(Wb), torch.from_numpy(d2t).to(DEV), k)
+    ora = vo.draft_head(hb, Wb, d2t, k)
+    assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
+    assert np.array_equal(g_ids, ora.ids)
+    assert np.max(np.abs(g_lp - ora.logp)) < 1e-3
+
+
 @pytest.mark.parametrize("rows", [1, 8, 64])
 def test_one_hot_hidden_state_is_bit_exact(rows):
     H, Vd, k = 1024, 2500, 7
