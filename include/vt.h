@@ -102,8 +102,9 @@ size_t vt_draft_head_workspace_bytes(int64_t rows, int64_t H, int64_t V_draft, i
 #define VT_WORKSPACE_HEADER_BYTES 8192
 vt_status vt_draft_head_workspace_init(void *workspace, size_t workspace_bytes, void *stream);
 
-/* Which kernel family serves this shape: 0 = streaming row-split kernels (memory bound,
- * rows <= 16), 1 = bf16 MFMA thin GEMM (rows > 16); -1 on invalid arguments. */
+/* Which kernel family serves this shape: 0 = streaming kernels that read W_sub once per group
+ * of 16 rows (memory bound: rows <= 16, and a few dozen rows at H = 2048 / 4096 and k <= 16),
+ * 1 = bf16 MFMA thin GEMM; -1 on invalid arguments. */
 int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
 
 /*

@@ -41,8 +41,10 @@ constexpr int kFewPlaneBytes = 64 * 16 + 5 * 16;  // an odd number of 16-byte pi
 constexpr int kFewLdsWl = 0;
 constexpr int few_lds_bytes(int nb) { return kFewLdsPart + 2 * nb * kGemvWaves * kFewPlaneBytes; }
 
-// KS: 32-column steps a wave multiplies per W_sub row (H = 512 * KS).
-template <int KS>
+// KS: 32-column steps a wave multiplies per W_sub row (H = 512 * KS).  SHARED: several workgroups
+// (one per group of 16 hidden states) stream the same W_sub rows side by side, so the loads leave
+// the lines in the cache for the neighbours instead of marking them as used once.
+template <int KS, bool SHARED>
 __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
 {
     constexpr int D = kFewSlots;
@@ -59,9 +61,24 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     const int g4 = lane >> 4;   // MFMA: which eight columns of a 32-column step; the result's rows 4 * g4 ..+3
     char* lds = reinterpret_cast<char*>(smem);
 
-    // rows of this workgroup: an even split of V_draft over the grid, in order
-    const int nb = gridDim.x;
-    const int b = blockIdx.x;
+    // More than 16 hidden states are served in groups of 16 by workgroups of their own: workgroup
+    // (b, sg) walks run b of W_sub for states 16 sg .. 16 sg + 15.  The workgroups of one run sit next
+    // to each other in launch order and on the same XCD (block number modulo 8), so all but the first
+    // to ask find the run's lines in that XCD's L2.
+    const int nsg = a.nsg;
+    const int nb = gridDim.x / nsg;  // runs of W_sub rows
+    int b, sg;
+    if ((nb & 7) == 0) {
+        const int y = blockIdx.x >> 3;
+        sg = y % nsg;
+        b = (y / nsg) * 8 + (blockIdx.x & 7);
+    } else {
+        sg = blockIdx.x % nsg;
+        b = blockIdx.x / nsg;
+    }
+    const int s0 = sg * 16;                                     // first hidden state of this workgroup
+    const int rows = a.rows - s0 < 16 ? a.rows - s0 : 16;       // and how many it serves
+    // rows of this workgroup: an even split of V_draft over the runs, in order
     const int base = a.Vd / nb;
     const int rem = a.Vd - base * nb;
     const int n_wg = base + (b < rem ? 1 : 0);
@@ -83,7 +100,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
 #pragma unroll
     for (int d = 0; d < KS; ++d) {
         const int r = ld_row + ((d & 1) ? 8 : 0);
-        hreg[d] = a.h[(size_t)(r < a.rows ? r : 0) * nchunk + wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
+        hreg[d] = a.h[(size_t)(s0 + (r < rows ? r : 0)) * nchunk + wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
     }
 
     // A operands.  Slot d of an iteration: block d / KS, 128-byte line (d % KS) / 2 of the wave's
@@ -96,7 +113,10 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         int r = blk * 16 + ld_row + ((d & 1) ? 8 : 0);
         r = r < n_wg ? r : n_wg - 1;
         const int piece = ((d % KS) >> 1) * 8 + ((d & 1) ? pc_b : pc_a);
-        buf[d] = __builtin_nontemporal_load(wbase + (size_t)r * nchunk + piece);
+        if constexpr (SHARED)
+            buf[d] = wbase[(size_t)r * nchunk + piece];
+        else
+            buf[d] = __builtin_nontemporal_load(wbase + (size_t)r * nchunk + piece);
     };
 #pragma unroll
     for (int d = 0; d < D; ++d) {
@@ -117,15 +137,15 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         const u32x4 x0 = st[m16 * 8 + (g4 ^ a_sw)];
         const u32x4 x1 = st[m16 * 8 + ((4 + g4) ^ a_sw)];
         __builtin_amdgcn_wave_barrier();
-        hreg[2 * c] = m16 < a.rows ? x0 : u32x4{0u, 0u, 0u, 0u};
-        hreg[2 * c + 1] = m16 < a.rows ? x1 : u32x4{0u, 0u, 0u, 0u};
+        hreg[2 * c] = m16 < rows ? x0 : u32x4{0u, 0u, 0u, 0u};
+        hreg[2 * c + 1] = m16 < rows ? x1 : u32x4{0u, 0u, 0u, 0u};
     }
 
-    // wave r < rows keeps hidden state r's results: the running list of its 16 best (lane q of every
+    // wave r < rows keeps the results of hidden state s0 + r: the running list of its 16 best (lane q of every
     // 16-lane row holds the q-th best) and, in lane c, the running maximum and sum of exponentials
     // over the block rows c it has seen
-    const int rows = a.rows;
     const bool mine = wave < rows;
+    const int state = s0 + wave;
     const int kth = a.k - 1;
     int lkey = kKeyNone, lidx = kIdxNone;
     int thr = kKeyNone;  // key of the list's k-th entry: a logit that does not beat it cannot be among the k best
@@ -195,7 +215,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
                 rs = d > 0.0f ? rs * e + 1.0f : rs + e;
                 rm = fmaxf(rm, z);
                 if (a.logits_out != nullptr && g4 == 0)
-                    a.logits_out[(size_t)wave * a.Vd + j0 + jb + m16] = z;
+                    a.logits_out[(size_t)state * a.Vd + j0 + jb + m16] = z;
             }
             // block rows that beat the list's k-th entry enter the list one by one, in row order
             // (ties keep the earlier, lower index ahead)
@@ -232,7 +252,7 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     // a result list goes to slot `slot` of the workspace: [slot][state] lists of 16 and one (max, sum) pair
     auto publish = [&](int slot) {
         if (mine) {
-            const size_t at = (size_t)slot * rows + wave;
+            const size_t at = (size_t)slot * a.rows + state;
             if (lane < 16) {
                 st_dev(a.part_val + at * 16 + lane, key2f(k64_key(best)));
                 st_dev(a.part_idx + at * 16 + lane, k64_idx(best));
@@ -254,13 +274,13 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         float2 st = make_float2(neg_inf(), 0.0f);
         const int li = lane >> 2;  // lane l: entries 4 * (l % 4) ..+3 of list l / 4
         if (li < count) {
-            const size_t at = ((size_t)(first + li) * rows + wave) * 16 + 4 * (lane & 3);
+            const size_t at = ((size_t)(first + li) * a.rows + state) * 16 + 4 * (lane & 3);
             coherent_load_issue(v, a.part_val + at);
             coherent_load_issue(ix, a.part_idx + at);
         }
         const bool act = lane < count;
         if (act)
-            coherent_load_issue(st, a.part_stat + (size_t)(first + lane) * rows + wave);
+            coherent_load_issue(st, a.part_stat + (size_t)(first + lane) * a.rows + state);
         coherent_load_wait(v, ix, st);
 #pragma unroll
         for (int q = 0; q < 4; ++q)
@@ -277,25 +297,29 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         const float lse = mm + __logf(ss);
         if (lane < a.k) {
             const int oi = k64_idx(best);
-            a.out_ids[(size_t)wave * a.k + lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
-            a.out_logp[(size_t)wave * a.k + lane] =
-                (key2f(k64_key(best)) - lse) + (a.parent != nullptr ? a.parent[wave] : 0.0f);
+            a.out_ids[(size_t)state * a.k + lane] = (oi != kIdxNone) ? a.d2t[oi] : -1;
+            a.out_logp[(size_t)state * a.k + lane] =
+                (key2f(k64_key(best)) - lse) + (a.parent != nullptr ? a.parent[state] : 0.0f);
         }
         if (lane == 0 && a.lse_out != nullptr)
-            a.lse_out[wave] = lse;
+            a.lse_out[state] = lse;
     };
 
-    const int P = gridDim.x;
-    const int grp = blockIdx.x >> 4;
+    // The workgroups of one group of states arrive in two levels (groups of 16, then the groups).
+    // Arrival counters in the workspace header: state group sg owns counters 1 + sg * (16 / nsg) ..
+    // for its groups of workgroups, and counter 0 (sg = 0) or 16 + sg for the call.
+    const int P = nb;
+    const int grp = b >> 4;
     const int ngrp = (P + 15) >> 4;
     const int in_grp = (grp == ngrp - 1) ? P - grp * 16 : 16;
+    unsigned int* call_ctr = a.arrive + (sg == 0 ? 0 : 16 + sg) * kArriveStrideWords;
     if (P == 1) {  // nothing to wait for
         emit();
         return;
     }
-    publish(blockIdx.x);
+    publish(b);
     if (tid == 0) {
-        unsigned int* ctr = a.arrive + (1 + grp) * kArriveStrideWords;
+        unsigned int* ctr = a.arrive + (1 + sg * (16 / nsg) + grp) * kArriveStrideWords;
         const unsigned int t = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = ((int)t == in_grp - 1) ? 1 : 0;
         if (last)
@@ -313,10 +337,10 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     }
     publish(P + grp);  // (every thread has read s_flag before this barrier)
     if (tid == 0) {
-        const unsigned int t = __hip_atomic_fetch_add(a.arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned int t = __hip_atomic_fetch_add(call_ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const int last = ((int)t == ngrp - 1) ? 1 : 0;
         if (last)
-            __hip_atomic_store(a.arrive, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(call_ctr, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         s_flag = last;
     }
     __syncthreads();
@@ -327,28 +351,33 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     emit();
 }
 
-// What the kernel assumes of a launch: 2..16 hidden states, lists of 16, at most 256 workgroups
-// (16 groups of 16) with their own and their groups' result slots in the workspace.
+// What the kernel assumes of a launch: 2..64 hidden states in nsg groups of 16, lists of 16, per group
+// of states at most 256 / nsg workgroups (16 / nsg groups of 16, so that the arrival counters fit the
+// workspace header), result slots for every workgroup and every group of workgroups.
 static bool few_rows_launch_ok(const Plan& p, const GemvArgs& ga)
 {
-    return p.few_rows && ga.rows >= 2 && ga.rows <= 16 && ga.KP == 16 && ga.k <= 16 && p.blocks >= 1 && p.blocks <= 256 &&
-           ga.P == p.blocks + 16 && ga.fused && (p.H == 2048 || p.H == 4096) && ga.nchunk == p.H / 8;
+    const int nsg = ga.nsg;
+    if (!(p.few_rows && ga.rows >= 2 && nsg >= 1 && nsg <= 4 && nsg == (ga.rows + 15) / 16))
+        return false;
+    const int nb = p.blocks / nsg;
+    return p.blocks == nb * nsg && nb >= 1 && nb <= 16 * (16 / nsg) && ga.KP == 16 && ga.k <= 16 && ga.P == nb + 16 &&
+           ga.fused && (p.H == 2048 || p.H == 4096) && ga.nchunk == p.H / 8;
 }
 
-template <int KS>
+template <int KS, bool SHARED>
 static hipError_t launch_few_t(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
     constexpr int lds = few_lds_bytes(kFewSlots / KS);
     static_assert(lds <= kGemvLdsLimit, "fits a compute unit's LDS");
     static std::atomic<int> raised{0};  // the dynamic LDS limit of this instantiation is raised once
     if (!raised.load()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_few_rows_kernel<KS>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_few_rows_kernel<KS, SHARED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess)
             return e;
         raised.store(1);
     }
-    hipLaunchKernelGGL((gemv_few_rows_kernel<KS>), dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
+    hipLaunchKernelGGL((gemv_few_rows_kernel<KS, SHARED>), dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
     return hipGetLastError();
 }
 
@@ -356,7 +385,9 @@ hipError_t launch_gemv_few_rows(const Plan& p, const GemvArgs& ga, hipStream_t s
 {
     if (!few_rows_launch_ok(p, ga))
         return hipErrorInvalidValue;
-    return p.H == 4096 ? launch_few_t<8>(p, ga, s) : launch_few_t<4>(p, ga, s);
+    if (ga.nsg > 1)
+        return p.H == 4096 ? launch_few_t<8, true>(p, ga, s) : launch_few_t<4, true>(p, ga, s);
+    return p.H == 4096 ? launch_few_t<8, false>(p, ga, s) : launch_few_t<4, false>(p, ga, s);
 }
 
 }  // namespace vt

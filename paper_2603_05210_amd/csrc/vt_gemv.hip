@@ -514,6 +514,7 @@ static void fill_gemv_args(const Plan& p, const HeadArgs& a, GemvArgs& ga)
     ga.KP = p.KP;
     ga.rpb = p.rpb;
     ga.ks = p.mfma ? p.ks : 1;
+    ga.nsg = p.few_rows ? p.nsg : 1;
     ga.part_val = a.part_val;
     ga.part_idx = a.part_idx;
     ga.part_stat = a.part_stat;

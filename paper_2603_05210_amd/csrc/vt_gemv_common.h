@@ -22,6 +22,7 @@ struct GemvArgs {
     uint16_t* h_out;        // test hook: normalised hidden state, or NULL
     int rows, nchunk, Vd, P, k, KP, rpb;  // rpb: W_sub rows per workgroup (multiple of J)
     int ks;  // slices of the hidden dimension whose partial logits sit side by side in LDS (1: none)
+    int nsg; // kernel for a few rows: groups of 16 hidden states, each served by workgroups of its own
     float* part_val;
     int32_t* part_idx;
     float2* part_stat;

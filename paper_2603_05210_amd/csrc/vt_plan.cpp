@@ -90,18 +90,24 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
         p.P = p.blocks;
         p.fused = 1;
         p.ks = 1;
-    } else if (rows >= 2 && rows <= kGemvMaxRows && p.KP <= 16 && (H == 2048 || H == 4096)) {
-        // 16 waves share each block of 16 W_sub rows, at most one workgroup per compute unit; the
-        // workspace holds a result slot per workgroup and one per group of 16 workgroups
+    } else if (rows >= 2 && rows <= kFewMaxRows && p.KP <= 16 && (H == 2048 || H == 4096) &&
+               (rows <= 32 || Vd <= kFewWideMaxVd)) {
+        // 16 waves share each block of 16 W_sub rows; every group of 16 rows has workgroups of its own
+        // (at most one workgroup per compute unit in all, a multiple of 8 per group so that the
+        // workgroups reading the same W_sub rows share an XCD); the workspace holds, per row, a result
+        // slot per workgroup of its group and one per 16 of them
+        static const int kRuns[4] = {256, 128, 80, 64};
         p.regime = 0;
         p.few_rows = 1;
+        p.nsg = (int)((rows + 15) / 16);
         p.KP = 16;
         p.NR = 16;
         p.J = 1;
         p.rpb = 0;
-        int blocks = (int)((Vd + 15) / 16);
-        p.blocks = blocks > kGemvTargetBlocks ? kGemvTargetBlocks : blocks;
-        p.P = p.blocks + 16;
+        int runs = (int)((Vd + 15) / 16);
+        runs = runs > kRuns[p.nsg - 1] ? kRuns[p.nsg - 1] : runs;
+        p.blocks = runs * p.nsg;
+        p.P = runs + 16;
         p.fused = 1;
         p.ks = 1;
     } else if (streaming) {

@@ -12,6 +12,10 @@ namespace vt {
 // Streaming regime (rows <= kGemvMaxRows): workgroups of kGemvThreads threads, each wave
 // streams groups of J consecutive W_sub rows.
 constexpr int kGemvMaxRows = 16;
+constexpr int kFewMaxRows = 64;  // the kernel for a few rows: up to four groups of 16 rows share the W_sub stream
+// three or four groups only over a narrow vocabulary (measured at H = 4096, 48 / 64 rows: 44 / 46 us
+// against the GEMM regime's 57 at V_draft = 13264, 88 / 94 against 85 at 32768)
+constexpr int kFewWideMaxVd = 16384;
 constexpr int kGemvThreads = 1024;
 constexpr int kGemvWaves = kGemvThreads / 64;
 constexpr int kGemvMaxRowsPerBlock = 512;  // W_sub rows one workgroup may own (8 logits per lane at the end)
@@ -36,7 +40,8 @@ struct Plan {
     int J;       // W_sub rows a wave reduces together
     int rpb;     // W_sub rows per workgroup
     int one_row; // the dedicated one-row kernel (H = 512, 1024, 2048 or 4096, lists of at most 16)
-    int few_rows; // the dedicated kernel for 2..16 rows (H = 2048 or 4096, lists of at most 16)
+    int few_rows; // the dedicated kernel for 2..kFewMaxRows rows (H = 2048 or 4096, lists of at most 16)
+    int nsg;     // its groups of 16 rows, each served by blocks / nsg workgroups
     int fused;   // the streaming kernel's last workgroup also does the final merge
     int mfma;    // matrix-core variant of the streaming kernel (several rows, H % 256 == 0)
     int ks;      // its slices of the hidden dimension per 16-row group (narrow ranges: keeps 16 waves busy)

@@ -92,7 +92,9 @@ def test_host_token_id_check():
 
 @pytest.mark.parametrize("rows,H,Vd,k,regime", [
     (1, 2048, 4096, 1, 0), (8, 2048, 128256, 10, 0), (16, 4096, 32000, 8, 0),
-    (17, 4096, 32000, 8, 1), (1024, 4096, 32000, 8, 1), (512, 4096, 128256, 16, 1),
+    (17, 4096, 32000, 8, 0), (32, 2048, 128256, 16, 0), (48, 4096, 13264, 10, 0), (48, 4096, 32000, 8, 1),
+    (17, 4096, 32000, 17, 1), (17, 1024, 32000, 8, 1), (65, 4096, 4096, 8, 1),
+    (1024, 4096, 32000, 8, 1), (512, 4096, 128256, 16, 1),
 ])
 def test_regime_and_workspace_query(rows, H, Vd, k, regime):
     assert vt.vt_draft_head_regime(rows, H, Vd, k) == regime

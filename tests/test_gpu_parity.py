@@ -159,6 +159,12 @@ FEW_ROWS = [
     (16, 2048, 5000, 4097, 16),
     (16, 4096, 9000, 8200, 16),  # 32 or 33 rows per workgroup: a ragged third block
     (4, 2048, 70000, 66001, 10),
+    # more than 16 rows: groups of 16 rows on workgroups of their own, side by side over the same W_sub rows
+    (17, 4096, 6000, 4099, 10),   # a second group of one row
+    (32, 4096, 3000, 2049, 8),    # two full groups; 128 runs of 16 or 17 rows
+    (40, 2048, 9000, 4380, 16),   # three groups (80 runs)
+    (64, 4096, 20000, 13264, 10),  # four groups
+    (33, 2048, 300, 100, 3),      # fewer runs than a multiple of 8: the plain block numbering
 ]
 
 
@@ -183,7 +189,7 @@ def test_few_rows_kernel_full_comparison(rows, H, V, Vd, k):
         assert np.array_equal(n_ids.cpu().numpy(), g_ids) and np.array_equal(n_lp.cpu().numpy(), g_lp)
 
 
-@pytest.mark.parametrize("rows,H", [(2, 4096), (7, 2048), (12, 4096), (16, 2048)])
+@pytest.mark.parametrize("rows,H", [(2, 4096), (7, 2048), (12, 4096), (16, 2048), (23, 4096), (64, 2048)])
 def test_exact_arithmetic_few_rows_kernel(rows, H):
     """Small-integer inputs through the kernel for 2..16 rows: logits bit for bit, ties (many) by draft index."""
     Vd, k = 5001, 12
