@@ -53,6 +53,10 @@ def parse_args():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain 1 GiB device copy a few times and exit (reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE profiler counters)")
+    ap.add_argument("--calibrate-gemm", action="store_true",
+                    help="time the vendor library's plain bf16 GEMM (torch.matmul: no softmax, no top-k, bf16 logits "
+                         "stored) on the two tree-drafting shapes, with the benchmark's operands and with constant "
+                         "ones: what a GEMM alone reaches on this GPU at these sizes")
     ap.add_argument("--select", action="store_true",
                     help="measure only the vocabulary-size selection call and exit")
     ap.add_argument("--operands", choices=("gaussian", "zero_h", "const"), default="gaussian",
@@ -75,6 +79,9 @@ def workloads():
     w.append(dict(name="cfg0", H=2048, rows=1, Vd=4096, k=1, peaked=0.0))
     for b in (1, 4, 8):
         w.append(dict(name="cfg1_B%d" % b, H=2048, rows=b, Vd=V, k=10, peaked=0.0))
+    # one tree-drafting step of one sequence (8 nodes) and of four (32 nodes) over the vocabulary Section 2.6 selects
+    w.append(dict(name="tree_rows8_Vd13264", H=4096, rows=8, Vd=13264, k=8, peaked=0.0))
+    w.append(dict(name="tree_rows32_Vd13264", H=4096, rows=32, Vd=13264, k=8, peaked=0.0))
     w.append(dict(name="cfg3", H=4096, rows=1024, Vd=32000, k=8, peaked=0.0))
     w.append(dict(name="cfg4", H=4096, rows=512, Vd=V, k=16, peaked=0.05))
     # the one-row step over a compressed W_sub, with its neighbours fused in, and the fusion layer ahead of it
@@ -252,7 +259,8 @@ class Runner:
 
 def report(w, st, cold, warm):
     nbytes, flops = algorithmic(w)
-    regime = "hbm" if (w["rows"] <= 16 or w.get("kind") == "fusion") else "mfma"   # the fusion layer at 64 rows is still 64 FLOP per byte
+    # up to 64 rows the step is bound by reading W_sub once (at most 64 FLOP per byte); so is the fusion layer at 64 rows
+    regime = "hbm" if (w["rows"] <= 64 or w.get("kind") == "fusion") else "mfma"
     t_s = cold["us_per_step"] * 1e-6   # dense-loop device time per step (wall clock if that is larger)
     gbs = nbytes / t_s / 1e9
     tfl = flops / t_s / 1e12
@@ -357,6 +365,40 @@ def calibrate_copy():
     print(json.dumps({"calibrate_copy_bytes": n, "reads": n, "writes": n, "launches": 5}))
 
 
+def calibrate_gemm(steps=50):
+    """Dense loop of torch.matmul(h, W_sub^T) on the cfg3 / cfg4 shapes (and a large square one)."""
+    import torch
+    from paper_2603_05210_amd import synth
+    dev = "cuda:0"
+    out = []
+    for name, rows, H, Vd in (("cfg3", 1024, 4096, 32000), ("cfg4", 512, 4096, synth.FULL_VOCAB), ("square_8192", 8192, 8192, 8192)):
+        for fill in ("gaussian", "const"):
+            if fill == "gaussian":
+                g = torch.Generator(device=dev).manual_seed(0)
+                h = torch.randn(rows, H, device=dev, generator=g).to(torch.bfloat16)
+                W = (torch.randn(Vd, H, device=dev, generator=g) * 0.02).to(torch.bfloat16)
+            else:
+                h = torch.full((rows, H), 1.0, device=dev, dtype=torch.bfloat16)
+                W = torch.full((Vd, H), 0.02, device=dev, dtype=torch.bfloat16)
+            z = torch.empty(rows, Vd, device=dev, dtype=torch.bfloat16)
+            for _ in range(10):
+                torch.matmul(h, W.t(), out=z)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(steps):
+                torch.matmul(h, W.t(), out=z)
+            e1.record()
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / steps
+            fl = 2.0 * rows * H * Vd
+            out.append({"shape": name, "rows": rows, "H": H, "V_draft": Vd, "operands": fill, "us_per_call": round(us, 1),
+                        "tflops": round(fl / us / 1e6, 1), "frac_of_2500": round(fl / us / 1e6 / 2500.0, 3)})
+            del h, W, z
+            torch.cuda.empty_cache()
+    print(json.dumps({"calibrate_gemm": out, "steps": steps, "library": "torch.matmul (hipBLASLt / rocBLAS)"}))
+
+
 def selector_bench(torch, vt, synth, dev, with_cpu, n_tokens=32 * 1024 * 1024, calls=5):
     """The vocabulary-size selection (Eq. 1-5) on a Zipf(1.1) stream over LLaMA-3's vocabulary
     with Table 1's constants: whole-call time (kernels + the call's one synchronisation)."""
@@ -408,6 +450,9 @@ def main():
     args = parse_args()
     if args.calibrate_copy:
         calibrate_copy()
+        return
+    if args.calibrate_gemm:
+        calibrate_gemm()
         return
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: the head runs on exactly one GPU here (the head shards by vocabulary or by rows "
