@@ -45,9 +45,9 @@ static vt_status run_head(const uint16_t* h, int64_t rows, int64_t H, const uint
     a.eps = ex.eps;
     a.parent = ex.parent;
     a.h_out = ex.h_out;
-    if (ex.gamma != nullptr && !p.one_row && !p.few_rows) {
-        // the kernels for one row and for a few rows normalise on the way in: the other shapes get a small
-        // kernel of their own, which leaves the normalised state behind the partial results in the workspace
+    if (ex.gamma != nullptr && !p.one_row) {
+        // only the one-row kernel normalises on the way in: the other shapes get a small kernel of
+        // their own, which leaves the normalised state behind the partial results in the workspace
         uint16_t* hn = ex.h_out != nullptr ? ex.h_out : reinterpret_cast<uint16_t*>(ws + p.total_bytes);
         if (launch_rmsnorm(h, ex.gamma, ex.eps, (int)rows, (int)H, hn, s) != hipSuccess)
             return VT_ERR_DEVICE;

@@ -39,9 +39,7 @@ constexpr int kFewLdsStage = 0;
 constexpr int kFewLdsPart = kGemvWaves * kFewStageBytes;  // 64 KiB
 constexpr int kFewPlaneBytes = 64 * 16 + 5 * 16;  // an odd number of 16-byte pieces: the four quarters of a read fall on two bank groups
 constexpr int kFewLdsWl = 0;
-constexpr int few_lds_planes(int nb) { return kFewLdsPart + 2 * nb * kGemvWaves * kFewPlaneBytes; }
-// after the planes: float[16 states][16 waves], the waves' sums of squares when the RMSNorm is done on the way in
-constexpr int few_lds_bytes(int nb) { return few_lds_planes(nb) + 16 * 16 * 4; }
+constexpr int few_lds_bytes(int nb) { return kFewLdsPart + 2 * nb * kGemvWaves * kFewPlaneBytes; }
 
 // KS: 32-column steps a wave multiplies per W_sub row (H = 512 * KS).  SHARED: several workgroups
 // (one per group of 16 hidden states) stream the same W_sub rows side by side, so the loads leave
@@ -104,14 +102,6 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         const int r = ld_row + ((d & 1) ? 8 : 0);
         hreg[d] = a.h[(size_t)(s0 + (r < rows ? r : 0)) * nchunk + wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
     }
-    // h is the state before the final RMSNorm: the matching pieces of the norm's weight
-    const bool norm = a.gamma != nullptr;
-    u32x4 gm[KS];
-    if (norm) {
-#pragma unroll
-        for (int d = 0; d < KS; ++d)
-            gm[d] = reinterpret_cast<const u32x4*>(a.gamma)[wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
-    }
 
     // A operands.  Slot d of an iteration: block d / KS, 128-byte line (d % KS) / 2 of the wave's
     // columns, rows 0..7 (even d) or 8..15 (odd d) of the block.  Rows past the workgroup's run
@@ -137,62 +127,6 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     u32x4* stage = reinterpret_cast<u32x4*>(lds + kFewLdsStage + wave * kFewStageBytes);
     float* part = reinterpret_cast<float*>(lds + kFewLdsPart);
     const int a_sw = (m16 >> 1) & 7;
-    if (norm) {
-        // RMSNorm on the way in, while the first W_sub pieces are on their way: a lane squares its
-        // pieces of states l / 8 (even loads) and l / 8 + 8 (odd loads), the 8 lanes of a state add up,
-        // the 16 waves' sums meet in LDS and every lane adds them in wave order;
-        // h = bf16((g * rsqrt(mean g^2 + eps)) * gamma)
-        float sq[2] = {0.0f, 0.0f};
-#pragma unroll
-        for (int d = 0; d < KS; ++d) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float lo = bf16_lo(hreg[d][q]), hi = bf16_hi(hreg[d][q]);
-                sq[d & 1] += lo * lo + hi * hi;
-            }
-        }
-        float* ssq = reinterpret_cast<float*>(lds + few_lds_planes(NB));  // [state][wave]
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            float v = sq[e];
-            v += xchg_f<1>(v, lane);
-            v += xchg_f<2>(v, lane);
-            v += xchg_f<4>(v, lane);
-            if ((lane & 7) == 0)
-                ssq[(ld_row + 8 * e) * kGemvWaves + wave] = v;
-        }
-        __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0) only
-        __builtin_amdgcn_s_barrier();
-        float rinv[2];
-#pragma unroll
-        for (int e = 0; e < 2; ++e) {
-            const f32x4* src = reinterpret_cast<const f32x4*>(ssq + (ld_row + 8 * e) * kGemvWaves);
-            float tot = 0.0f;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const f32x4 t = src[q];
-                tot += t[0];
-                tot += t[1];
-                tot += t[2];
-                tot += t[3];
-            }
-            rinv[e] = 1.0f / __builtin_sqrtf(tot / (float)(nchunk * 8) + a.eps);
-        }
-#pragma unroll
-        for (int d = 0; d < KS; ++d) {
-            const float r = rinv[d & 1];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const float lo = (bf16_lo(hreg[d][q]) * r) * bf16_lo(gm[d][q]);
-                const float hi = (bf16_hi(hreg[d][q]) * r) * bf16_hi(gm[d][q]);
-                hreg[d][q] = f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
-            }
-            const int st_r = ld_row + ((d & 1) ? 8 : 0);
-            if (a.h_out != nullptr && b == 0 && st_r < rows)  // test hook: the normalised states, written once
-                reinterpret_cast<u32x4*>(a.h_out)[(size_t)(s0 + st_r) * nchunk + wave * (KS * 4) + (d >> 1) * 8 +
-                                                  ((d & 1) ? pc_b : pc_a)] = hreg[d];
-        }
-    }
     // the hidden states become fragments while the first W_sub pieces are on their way
 #pragma unroll
     for (int c = 0; c < KS / 2; ++c) {

@@ -81,7 +81,7 @@ FUSED = [
     (1, 4096, 14000, 13264, 10),
     (1, 264, 2000, 1500, 3),       # one row through the generic streaming kernel
     (2, 1024, 9000, 4099, 5),
-    (8, 2048, 12000, 9001, 16),      # normalised inside the kernel for a few rows
+    (8, 2048, 12000, 9001, 16),      # the kernel for a few rows behind the separate norm kernel
     (10, 4096, 20000, 13264, 8),
     (24, 4096, 6000, 4099, 10),      # two groups of rows
     (16, 4096, 300, 100, 3),         # fewer W_sub rows per workgroup than waves
