@@ -421,6 +421,10 @@ def selector_bench(torch, vt, synth, dev, with_cpu, n_tokens=32 * 1024 * 1024, c
     out = dict(workload="select_vocab: V=%d d=%d n_tokens=%d Zipf(1.1) alpha=%g c_min=%g" % (V, d, n_tokens, alpha, c_min),
                ms_per_call=ms, Mtokens_per_s=n_tokens / ms / 1e3, stream_GBps=4.0 * n_tokens / (ms * 1e-3) / 1e9,
                k_star=int(res.k_star), C=res.C, R=res.R, U=res.U)
+    # both calls are bound by reading the 4-byte token stream once: achieved = stream bytes over the whole
+    # call (for the selection that includes ranking 128 Ki frequencies and the call's synchronisation)
+    out["roofline"] = dict(bound="hbm", achieved=out["stream_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                           frac=out["stream_GBps"] / HBM_PEAK_GBS, traffic=None)
     # coverage of the selected vocabulary on the same stream (Table 4's two ratios)
     _, _, _, ids = vt.vt_select_vocab(t_dev, V, d, F_fixed, alpha, c_min, k_min, V, workspace=ws)
     t2d = vt.vt_build_t2d(ids.contiguous(), V)
@@ -435,6 +439,8 @@ def selector_bench(torch, vt, synth, dev, with_cpu, n_tokens=32 * 1024 * 1024, c
     out["coverage"] = dict(ms_per_call=cms, Mtokens_per_s=n_tokens / cms / 1e3,
                            stream_GBps=4.0 * n_tokens / (cms * 1e-3) / 1e9, freq_coverage=cov.freq_coverage,
                            unique_coverage=cov.unique_coverage)
+    out["coverage"]["roofline"] = dict(bound="hbm", achieved=out["coverage"]["stream_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                                       frac=out["coverage"]["stream_GBps"] / HBM_PEAK_GBS, traffic=None)
     if with_cpu:
         from oracle import vs_oracle as vs
         sample = tokens[: 8 * 1024 * 1024]

@@ -101,6 +101,72 @@ __global__ void __launch_bounds__(kHistThreads) hist_kernel(const int32_t* __res
     }
 }
 
+// Long streams over a vocabulary of at most kRangeClasses * kRangeBins ids: the ids are cut into
+// classes of kRangeBins consecutive ids, a workgroup owns one class and one slice of the stream and
+// counts its class in a plain LDS histogram (no tags, no probing, one LDS atomic per token of the
+// class; the other tokens are dropped).  Every slice is read by one workgroup per class; they are
+// neighbours in launch order and sit on the same XCD (block number modulo 8), so the slice comes
+// from HBM once and from that XCD's L2 for the rest.
+constexpr int kRangeBins = 32768;   // 128 KiB of LDS
+constexpr int kRangeClasses = 8;
+constexpr int64_t kRangeMinTokens = 1 << 20;
+
+__global__ void __launch_bounds__(kHistThreads) hist_range_kernel(const int32_t* __restrict__ tokens, int64_t n, int V,
+                                                                  int ncls, uint32_t* __restrict__ freq,
+                                                                  int* __restrict__ err)
+{
+    extern __shared__ int hist_lds[];
+    uint32_t* bins = reinterpret_cast<uint32_t*>(hist_lds);
+    for (int i = threadIdx.x; i < kRangeBins; i += kHistThreads)
+        bins[i] = 0u;
+    __syncthreads();
+    const int nslices = gridDim.x / ncls;
+    int cls, slice;
+    if ((nslices & 7) == 0) {
+        const int y = blockIdx.x >> 3;
+        cls = y % ncls;
+        slice = (y / ncls) * 8 + (blockIdx.x & 7);
+    } else {
+        cls = blockIdx.x % ncls;
+        slice = blockIdx.x / ncls;
+    }
+    const int base = cls * kRangeBins;
+    const bool checks = cls == 0;  // the class-0 workgroup of a slice reports ids outside [0, V)
+    bool bad = false;
+    auto count = [&](int t) {
+        const unsigned int u = (unsigned int)(t - base);
+        if (u < (unsigned int)kRangeBins && t < V)
+            atomicAdd(&bins[u], 1u);
+        if (checks)
+            bad |= (t < 0 || t >= V);
+    };
+    const int64_t per = ((n + nslices - 1) / nslices + 3) & ~(int64_t)3;  // whole 16-byte pieces per slice
+    const int64_t lo = (int64_t)slice * per;
+    const int64_t hi = lo + per < n ? lo + per : n;
+    if (lo < hi) {
+        typedef int i32x4 __attribute__((ext_vector_type(4)));
+        const i32x4* t4 = reinterpret_cast<const i32x4*>(tokens);
+        const int64_t a1 = hi & ~(int64_t)3;
+        for (int64_t i = (lo >> 2) + threadIdx.x; i < (a1 >> 2); i += kHistThreads) {
+            const i32x4 q = t4[i];
+            count(q.x);
+            count(q.y);
+            count(q.z);
+            count(q.w);
+        }
+        for (int64_t i = a1 + threadIdx.x; i < hi; i += kHistThreads)
+            count(tokens[i]);
+    }
+    if (bad)
+        atomicOr(err, 1);
+    __syncthreads();
+    for (int i = threadIdx.x; i < kRangeBins; i += kHistThreads) {
+        const uint32_t c = bins[i];
+        if (c != 0u)
+            atomicAdd(&freq[base + i], c);
+    }
+}
+
 // ------------------------------------------------------------------ sort by (frequency desc, id asc)
 // key = frequency << 32 | (0xFFFFFFFF - id): descending keys are the wanted order; padding
 // keys are 0 and sink to the end (a real key is never 0: its low word is >= 0x80000000).
@@ -478,10 +544,26 @@ hipError_t launch_select(const int32_t* tokens, int64_t n, int V, const SelectPa
             return e;
         lds_raised.store(true);
     }
-    int64_t hb = (n + (int64_t)kHistThreads * 64 - 1) / ((int64_t)kHistThreads * 64);
-    if (hb > 256)
-        hb = 256;
-    hipLaunchKernelGGL(hist_kernel, dim3((unsigned)hb), dim3(kHistThreads), hist_lds, s, tokens, n, V, freq, err);
+    const int ncls = (V + kRangeBins - 1) / kRangeBins;
+    if (n >= kRangeMinTokens && ncls <= kRangeClasses) {
+        constexpr size_t range_lds = (size_t)kRangeBins * sizeof(uint32_t);
+        static std::atomic<bool> range_raised{false};
+        if (!range_raised.load()) {
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(hist_range_kernel),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)range_lds);
+            if (e != hipSuccess)
+                return e;
+            range_raised.store(true);
+        }
+        const int nslices = 256 / ncls / 8 * 8;  // a multiple of 8 slices: one workgroup per compute unit at most
+        hipLaunchKernelGGL(hist_range_kernel, dim3((unsigned)(nslices * ncls)), dim3(kHistThreads), range_lds, s, tokens,
+                           n, V, ncls, freq, err);
+    } else {
+        int64_t hb = (n + (int64_t)kHistThreads * 64 - 1) / ((int64_t)kHistThreads * 64);
+        if (hb > 256)
+            hb = 256;
+        hipLaunchKernelGGL(hist_kernel, dim3((unsigned)hb), dim3(kHistThreads), hist_lds, s, tokens, n, V, freq, err);
+    }
 
     hipLaunchKernelGGL(make_keys_kernel, dim3((L.N2 + 255) / 256), dim3(256), 0, s, freq, V, L.N2, keys);
     const int chunks = L.N2 / kSortChunk;

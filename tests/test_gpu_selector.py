@@ -116,6 +116,23 @@ def test_out_of_range_token_is_reported():
     assert e.value.status == 4
 
 
+@pytest.mark.parametrize("V,n", [(70_000, 1_500_001), (40_000, 1_048_576), (32_768, 2_000_003), (200_000, 1_200_000)])
+def test_long_stream_histogram_by_id_classes(V, n):
+    """Streams of a million tokens and more are counted per class of 32768 ids in plain LDS histograms:
+    frequencies equal the oracle's for 1..7 classes and a ragged stream end, and ids outside [0, V) anywhere
+    in the stream are reported."""
+    _say("long stream V=%d n=%d" % (V, n))
+    tokens = synth.zipf_token_stream(V + 7, V, n)
+    res, freq, rank_ids, token_ids = vt.vt_select_vocab(torch.from_numpy(tokens).to(DEV), V, 256, 1.0e6, 0.5, 0.5, 1, V)
+    assert np.array_equal(freq.cpu().numpy(), vs.token_frequencies(tokens, V))
+    for pos, bad in ((n - 1, V), (n // 2 + 1, -3), (5, V + 40_000)):
+        t2 = tokens.copy()
+        t2[pos] = bad
+        with pytest.raises(vt.VtError) as e:
+            vt.vt_select_vocab(torch.from_numpy(t2).to(DEV), V, 256, 1.0e6, 0.5, 0.5, 1, V)
+        assert e.value.status == 4
+
+
 def test_repeated_calls_reuse_the_workspace():
     V = 9000
     ws = torch.empty(vt.vt_select_vocab_workspace_bytes(V), dtype=torch.uint8, device=DEV)
