@@ -278,7 +278,8 @@ def test_results_do_not_depend_on_run(capsys):
         assert np.array_equal(a[2].view(np.uint32), b[2].view(np.uint32))
 
 
-@pytest.mark.parametrize("rows,H,Vd,k", [(1, 1024, 30011, 10), (6, 512, 9001, 4), (300, 512, 3000, 8)])
+@pytest.mark.parametrize("rows,H,Vd,k", [(1, 1024, 30011, 10), (6, 512, 9001, 4), (300, 512, 3000, 8),
+                                         (8, 4096, 9001, 8), (24, 2048, 5000, 10)])
 def test_hip_graph_replays_match_eager(rows, H, Vd, k):
     """A captured draft step replays correctly (several replays, eager work in between): the
     step allocates nothing, takes no host round trip and its fused merge re-arms itself."""
@@ -337,6 +338,40 @@ def test_calls_on_two_streams_do_not_disturb_each_other():
     for n in range(40):
         for si, st in enumerate(streams):
             _, r, ws, ids, lp = slots[si * 40 + n]
+            with torch.cuda.stream(st):
+                vt.vt_draft_head(hs[r], W_dev, d2t_dev, k, ids, lp, ws)
+    torch.cuda.synchronize()
+    for si, r, ws, ids, lp in slots:
+        assert np.array_equal(ids.cpu().numpy(), alone[r][0])
+        assert np.array_equal(lp.cpu().numpy().view(np.uint32), alone[r][1].view(np.uint32))
+
+
+def test_few_row_calls_on_two_streams_do_not_disturb_each_other():
+    """The same for the kernel that serves a few rows (8 rows and 20 rows: one and two groups of rows),
+    whose arrival counters (groups of workgroups, groups of rows) also live in the call's own workspace."""
+    H, Vd, k = 2048, 9000, 10
+    W_dev = to_dev_bf16(synth.gen_W(79, Vd, H, std=0.05))
+    d2t_dev = torch.arange(Vd, dtype=torch.int32, device=DEV)
+    hs = {r: to_dev_bf16(synth.gen_h(70 + r, r, H)) for r in (8, 20)}
+    alone = {}
+    for r, h in hs.items():
+        assert vt.vt_draft_head_regime(r, H, Vd, k) == 0
+        a, b = vt.vt_draft_head(h, W_dev, d2t_dev, k)
+        torch.cuda.synchronize()
+        alone[r] = (a.cpu().numpy(), b.cpu().numpy())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]   # default priority
+    slots = []
+    for si, st in enumerate(streams):
+        for n in range(30):
+            r = (8, 20)[(n + si) % 2]
+            ws = vt.new_workspace(vt.vt_draft_head_workspace_bytes(r, H, Vd, k), DEV)
+            ids = torch.empty((r, k), dtype=torch.int32, device=DEV)
+            lp = torch.empty((r, k), dtype=torch.float32, device=DEV)
+            slots.append((si, r, ws, ids, lp))
+    torch.cuda.synchronize()
+    for n in range(30):
+        for si, st in enumerate(streams):
+            _, r, ws, ids, lp = slots[si * 30 + n]
             with torch.cuda.stream(st):
                 vt.vt_draft_head(hs[r], W_dev, d2t_dev, k, ids, lp, ws)
     torch.cuda.synchronize()
