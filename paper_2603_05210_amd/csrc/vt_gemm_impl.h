@@ -246,7 +246,12 @@ __device__ __forceinline__ void store_epilogue(f32x16 (&acc)[SV * SR], const Gem
     });
 }
 
-template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K, bool STORE = false>
+// RS: K tiles in flight from memory, each in a set of staging registers of its own.  One suits a grid
+// that fills the chip several times over (several workgroups per compute unit hide each other's
+// latency); a grid of at most one workgroup per compute unit is bound by the latency of its own K
+// loop (a K tile of the small tiles is a few hundred cycles of MFMA work, a load takes a thousand
+// and more), and more tiles in flight shorten every one of its K tiles.
+template <int WV, int WR, int SV, int SR, int KP, bool GUARD_K, bool STORE = false, int RS = 1>
 __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
 {
     constexpr int BMV = WV * SV * 32;    // draft tokens per workgroup tile
@@ -304,24 +309,25 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
     });
     const int st_off = lrow * 8 + (lc ^ ((lrow >> 1) & 7));
 
-    u32x4 stage[NLD];
-    auto load_one = [&](int kt, auto I) {
+    u32x4 stage[RS][NLD];  // K tile t travels through register set t % RS
+    auto load_one = [&](int kt, auto ST, auto I) {
         constexpr int i = decltype(I)::value;
+        constexpr int st = decltype(ST)::value;
         const char* base = (i < NLD_W ? w_base : h_base) + (size_t)kt * 128;
         const u32x4* src = reinterpret_cast<const u32x4*>(base + goff[i]);
         if constexpr (GUARD_K) {
             const u32x4 zero = {0u, 0u, 0u, 0u};
-            stage[i] = ((kt * 8 + lc) < nchunk) ? *src : zero;
+            stage[st][i] = ((kt * 8 + lc) < nchunk) ? *src : zero;
         } else {
-            stage[i] = *src;
+            stage[st][i] = *src;
         }
     };
-    auto store_one = [&](u32x4* __restrict__ wr, auto I) {
+    auto store_one = [&](u32x4* __restrict__ wr, auto ST, auto I) {
         constexpr int i = decltype(I)::value;
-        wr[st_off + i * RSTEP * 8] = stage[i];
+        wr[st_off + i * RSTEP * 8] = stage[decltype(ST)::value][i];
     };
-    auto load_stage = [&](int kt) { static_for<NLD>([&](auto I) { load_one(kt, I); }); };
-    auto store_stage = [&](u32x4* __restrict__ wr) { static_for<NLD>([&](auto I) { store_one(wr, I); }); };
+    auto load_stage = [&](int kt, auto ST) { static_for<NLD>([&](auto I) { load_one(kt, ST, I); }); };
+    auto store_stage = [&](u32x4* __restrict__ wr, auto ST) { static_for<NLD>([&](auto I) { store_one(wr, ST, I); }); };
 
     // ---- fragment addressing ----
     const int frow = lane & 31;
@@ -337,8 +343,8 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
     });
 
     // Pipeline per K tile (4 K-steps of 16): tile kt is computed from LDS buffer kt%2.
-    //   step 0: tile kt+1 (in the staging registers since the previous iteration) -> other buffer
-    //   step 1: request tile kt+2 from memory into the staging registers
+    //   steps 0-2: tile kt+1 (in its staging registers since RS iterations ago) -> other buffer, and the
+    //   same registers request tile kt+1+RS from memory
     //   one barrier between steps 2 and 3: by then every wave has issued its last read of this
     //   buffer and finished its writes of the other one, so step 3 can already fetch the next
     //   tile's first fragments, and the next iteration may overwrite this buffer.
@@ -384,7 +390,7 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
     constexpr int TSTEPS = 3;                           // K-steps that carry staging turnover
     constexpr int NPAIR = (NLD + TSTEPS - 1) / TSTEPS;  // staging pieces turned over per such K-step
     auto k_step = [&](auto SET, auto KS, auto KSN, const u32x4* __restrict__ rd_next, auto DO_READ,
-                      u32x4* __restrict__ wr, auto DO_WRITE, int kt_load, auto DO_LOAD) {
+                      u32x4* __restrict__ wr, auto DO_WRITE, int kt_load, auto DO_LOAD, auto ST) {
         constexpr int set = decltype(SET)::value;
         constexpr int ks = decltype(KS)::value;
         constexpr bool do_read = decltype(DO_READ)::value;
@@ -409,9 +415,9 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
                     constexpr int i = ks * NPAIR + pr;
                     if constexpr (pr < NPAIR && i < NLD) {
                         if constexpr (do_write)
-                            store_one(wr, std::integral_constant<int, i>{});
+                            store_one(wr, ST, std::integral_constant<int, i>{});
                         if constexpr (do_load)
-                            load_one(kt_load, std::integral_constant<int, i>{});
+                            load_one(kt_load, ST, std::integral_constant<int, i>{});
                     }
                 });
             }
@@ -419,39 +425,68 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
         });
     };
 
-    // Two-stage pipeline per K tile (4 K-steps of 16): tile kt is computed from LDS buffer kt%2
-    // while, during K-steps 0-2, tile kt+1 moves from the staging registers into the other buffer
-    // and tile kt+2 is requested.  One barrier between K-steps 2 and 3: by then every wave has
-    // issued its last read of this buffer and finished its writes of the other one, so K-step 3
-    // can already fetch the next tile's first fragments and the next iteration may overwrite
-    // this buffer.
-    auto k_tile = [&](int kt, auto HAS1, auto HAS2) {
+    // Two LDS buffers per K tile (4 K-steps of 16): tile kt is computed from LDS buffer kt%2
+    // while, during K-steps 0-2, tile kt+1 moves from its staging registers (set ST) into the other
+    // buffer and tile kt+1+RS is requested into them.  One barrier between K-steps 2 and 3: by then
+    // every wave has issued its last read of this buffer and finished its writes of the other one, so
+    // K-step 3 can already fetch the next tile's first fragments and the next iteration may overwrite
+    // this buffer.  HAS1: tile kt+1 exists; HAS2: tile kt+1+RS exists.
+    auto k_tile = [&](int kt, auto ST, auto HAS1, auto HAS2) {
         // The two LDS buffers never overlap: say so, or the scheduler keeps every fragment
         // read behind the tile writes.
         const u32x4* __restrict__ rd = smem + (kt & 1) * STAGE;
         u32x4* __restrict__ wr = smem + ((kt & 1) ^ 1) * STAGE;
-        k_step(C0{}, C0{}, C1{}, rd, std::true_type{}, wr, HAS1, kt + 2, HAS2);
-        k_step(C1{}, C1{}, C2{}, rd, std::true_type{}, wr, HAS1, kt + 2, HAS2);
-        k_step(C0{}, C2{}, C3{}, rd, std::true_type{}, wr, HAS1, kt + 2, HAS2);
+        k_step(C0{}, C0{}, C1{}, rd, std::true_type{}, wr, HAS1, kt + 1 + RS, HAS2, ST);
+        k_step(C1{}, C1{}, C2{}, rd, std::true_type{}, wr, HAS1, kt + 1 + RS, HAS2, ST);
+        k_step(C0{}, C2{}, C3{}, rd, std::true_type{}, wr, HAS1, kt + 1 + RS, HAS2, ST);
         __syncthreads();
-        k_step(C1{}, C3{}, C0{}, smem + ((kt & 1) ^ 1) * STAGE, HAS1, wr, std::false_type{}, 0, std::false_type{});
+        k_step(C1{}, C3{}, C0{}, smem + ((kt & 1) ^ 1) * STAGE, HAS1, wr, std::false_type{}, 0, std::false_type{}, ST);
+    };
+    // iteration kt with the register set (kt + 1) % RS picked at run time (the loop's first and last iterations)
+    auto k_tile_any = [&](int kt) {
+        static_for<RS>([&](auto ST) {
+            if ((kt + 1) % RS == decltype(ST)::value) {
+                if (kt + 1 + RS < KT)
+                    k_tile(kt, ST, std::true_type{}, std::true_type{});
+                else if (kt + 1 < KT)
+                    k_tile(kt, ST, std::true_type{}, std::false_type{});
+                else
+                    k_tile(kt, ST, std::false_type{}, std::false_type{});
+            }
+        });
     };
 
-    load_stage(0);
-    store_stage(smem);
-    if (KT > 1)
-        load_stage(1);
+    // tiles 0 .. RS-1 are requested together; tile 0 goes to LDS and its registers request tile RS
+    static_for<RS>([&](auto ST) {
+        if (decltype(ST)::value < KT)
+            load_stage(decltype(ST)::value, ST);
+    });
+    store_stage(smem, C0{});
+    if (RS < KT)
+        load_stage(RS, C0{});
     __syncthreads();
     read_frags(smem, C0{}, C0{});
     {
         int kt = 0;
-        for (; kt + 2 < KT; ++kt)
-            k_tile(kt, std::true_type{}, std::true_type{});
-        if (kt + 1 < KT) {
-            k_tile(kt, std::true_type{}, std::false_type{});
-            ++kt;
+        if constexpr (RS == 1) {
+            for (; kt + 2 < KT; ++kt)
+                k_tile(kt, C0{}, std::true_type{}, std::true_type{});
+            if (kt + 1 < KT) {
+                k_tile(kt, C0{}, std::true_type{}, std::false_type{});
+                ++kt;
+            }
+            k_tile(kt, C0{}, std::false_type{}, std::false_type{});
+        } else {
+            // groups of RS iterations whose register sets are known at compile time: iteration kt + j uses
+            // set (j + 1) % RS (kt is a multiple of RS) and all of them have tiles left to move and to request
+            for (; kt + 2 * RS < KT; kt += RS)
+                static_for<RS>([&](auto J) {
+                    k_tile(kt + decltype(J)::value, std::integral_constant<int, (decltype(J)::value + 1) % RS>{},
+                           std::true_type{}, std::true_type{});
+                });
+            for (; kt < KT; ++kt)
+                k_tile_any(kt);
         }
-        k_tile(kt, std::false_type{}, std::false_type{});
     }
 
     if constexpr (STORE)
@@ -460,8 +495,8 @@ __global__ void __launch_bounds__(WV* WR * 64) gemm_head_kernel(GemmArgs a)
         head_epilogue<WV, WR, SV, SR, KP, (SV * SR > 8)>(acc, a, smem, v0, r0, vt_i, wave, lane);
 }
 
-template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD, bool STORE = false>
-static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
+template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD, bool STORE, int RS>
+static hipError_t launch_tile_rs(const Plan& p, const GemmArgs& ga, hipStream_t s)
 {
     constexpr int BMV = WV * SV * 32, BNR = WR * SR * 32, NT = WV * WR * 64;
     constexpr size_t lds_loop = (size_t)2 * (BMV + BNR) * 128;  // two operand stages
@@ -470,10 +505,10 @@ static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
     constexpr size_t lds = lds_loop > lds_epi ? lds_loop : lds_epi;
     static_assert(lds <= 160 * 1024, "operand stages and epilogue staging must fit the LDS");
     const bool guard = (p.H % 64) != 0;
-    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false, STORE>;
+    void (*kern)(GemmArgs) = gemm_head_kernel<WV, WR, SV, SR, KP, false, STORE, RS>;
     if constexpr (ALLOW_GUARD) {
         if (guard)
-            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true, STORE>;
+            kern = gemm_head_kernel<WV, WR, SV, SR, KP, true, STORE, RS>;
     } else {
         if (guard)
             return hipErrorInvalidValue;
@@ -488,6 +523,18 @@ static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
     }
     hipLaunchKernelGGL(kern, dim3(p.blocks), dim3(NT), lds, s, ga);
     return hipGetLastError();
+}
+
+// The small tiles keep several K tiles in flight when the grid gives a compute unit at most one workgroup.
+template <int WV, int WR, int SV, int SR, int KP, bool ALLOW_GUARD, bool STORE = false>
+static hipError_t launch_tile(const Plan& p, const GemmArgs& ga, hipStream_t s)
+{
+    constexpr bool small = WV * SV * WR * SR < 32;  // not the 256 x 256 tile
+    if constexpr (small) {
+        if (p.n_vtiles * p.n_rtiles <= 256)
+            return launch_tile_rs<WV, WR, SV, SR, KP, ALLOW_GUARD, STORE, (WV * SV * WR * SR >= 16 ? 3 : 4)>(p, ga, s);
+    }
+    return launch_tile_rs<WV, WR, SV, SR, KP, ALLOW_GUARD, STORE, 1>(p, ga, s);
 }
 
 template <int KP>

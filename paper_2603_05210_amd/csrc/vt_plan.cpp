@@ -50,6 +50,13 @@ int gemm_pick_tile(int rows, int H, int Vd, int KP)
     // the large tile has no K-tail variant and no room for long candidate lists
     if (KP > 16 || rows <= 128 || (H % 64) != 0)
         return 0;
+    // a grid of large tiles that leaves a quarter of the compute units idle: the time of the step is the
+    // time of one tile's whole K loop, which the 128 x 128 tile walks twice as fast (measured at H = 4096:
+    // 512 rows x 13 264 tokens 114 -> 98 us, 256 x 13 264 109 -> 68, 1024 x 4380 119 -> 92; from 208 large
+    // tiles on -- 1024 x 13 264 -- the large tile wins, 142 vs 178 us)
+    const int large = ((Vd + 255) / 256) * ((rows + 255) / 256);
+    if (large < 192)
+        return 0;
     return 1;
 }
 
