@@ -88,6 +88,9 @@ def workloads():
     for vd in (13264, V):
         w.append(dict(name="fp8_Vd%d" % vd, kind="head_q", fmt=1, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
         w.append(dict(name="mxfp4_Vd%d" % vd, kind="head_q", fmt=2, H=4096, rows=1, Vd=vd, k=10, peaked=0.0))
+    # a tree-drafting step of 8 nodes over the compressed forms
+    w.append(dict(name="fp8_rows8_Vd13264", kind="head_q", fmt=1, H=4096, rows=8, Vd=13264, k=8, peaked=0.0))
+    w.append(dict(name="mxfp4_rows8_Vd13264", kind="head_q", fmt=2, H=4096, rows=8, Vd=13264, k=8, peaked=0.0))
     w.append(dict(name="fused_Vd13264", kind="head_fused", H=4096, rows=1, Vd=13264, k=10, peaked=0.0))
     w.append(dict(name="fused_rows8_Vd13264", kind="head_fused", H=4096, rows=8, Vd=13264, k=8, peaked=0.0))
     w.append(dict(name="fusion_B1", kind="fusion", H=4096, rows=1, Vd=4096, k=1, peaked=0.0))

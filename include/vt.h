@@ -226,11 +226,12 @@ vt_status vt_build_subset_q(const uint16_t *full_W, int64_t V, int64_t H, const 
 /*
  * One draft step over a compressed W_sub: vt_draft_head's computation with every weight taken
  * as its code's value times its scale (bf16 hidden state, exact products, fp32 accumulation; the
- * scale multiplies the fp32 sum of its row or 32-weight block).  Served shapes: rows == 1 (the
- * memory-bound regime the compression is for), k <= 16, V_draft <= 262144, H in {1024, 2048,
- * 4096} (FP8) or {2048, 4096} (MXFP4); anything else is VT_ERR_SHAPE (VT_ERR_K for k).  Pointers,
+ * scale multiplies the fp32 sum of its row or 32-weight block).  Served shapes (the memory-bound
+ * regime the compression is for), k <= 16 throughout: rows == 1 with V_draft <= 262144 and H in
+ * {1024, 2048, 4096} (FP8) or {2048, 4096} (MXFP4); 2 <= rows <= 32 (up to 64 when V_draft <= 16384)
+ * with H in {2048, 4096} (FP8) or H == 4096 (MXFP4); anything else is VT_ERR_SHAPE (VT_ERR_K for k).  Pointers,
  * workspace rules (vt_draft_head_workspace_init once), asynchrony and outputs as vt_draft_head;
- * the _debug form also stores logits_out[V_draft] and lse_out[1] (either may be NULL).
+ * the _debug form also stores logits_out[rows][V_draft] and lse_out[rows] (either may be NULL).
  */
 size_t vt_draft_head_q_workspace_bytes(int fmt, int64_t rows, int64_t H, int64_t V_draft, int k);
 vt_status vt_draft_head_q(const uint16_t *h, int64_t rows, int64_t H, const uint8_t *codes, const void *scales,

@@ -30,7 +30,6 @@
 
 namespace vt {
 
-constexpr int kFewSlots = 8;                // 1 KiB load instructions in flight per wave
 constexpr int kFewStageBytes = 2 * 2048;    // per wave: two staging areas of 16 rows x 128 bytes
 // LDS map (bytes): staging areas, then two planes of partial sums for each of the NB blocks of an
 // iteration (per wave 64 lanes x 16 bytes, one spare piece per 16 lanes); once the stream has ended
@@ -41,16 +40,58 @@ constexpr int kFewPlaneBytes = 64 * 16 + 5 * 16;  // an odd number of 16-byte pi
 constexpr int kFewLdsWl = 0;
 constexpr int few_lds_bytes(int nb) { return kFewLdsPart + 2 * nb * kGemvWaves * kFewPlaneBytes; }
 
-// KS: 32-column steps a wave multiplies per W_sub row (H = 512 * KS).  SHARED: several workgroups
-// (one per group of 16 hidden states) stream the same W_sub rows side by side, so the loads leave
-// the lines in the cache for the neighbours instead of marking them as used once.
-template <int KS, bool SHARED>
+// How W_sub is stored (FMT 0: bf16; VT_Q_FP8_E4M3: one byte per weight and an fp32 scale per row;
+// VT_Q_MXFP4: two weights per byte and an exponent byte per 32 weights) and what follows from it
+// for a wave's share of a row -- H / 16 columns, whole 128-byte lines in every served case.
+template <int FMT, int H>
+struct FewGeom {
+    static constexpr int kCols = H / 16;                                          // columns per wave
+    static constexpr int kRowBytes = FMT == 0 ? H * 2 : FMT == VT_Q_FP8_E4M3 ? H : H / 2;
+    static constexpr int kPieces = kRowBytes / 16;                                // 16-byte pieces per W_sub row
+    static constexpr int kLines = kRowBytes / 16 / 128;                           // 128-byte lines per wave and row
+    static constexpr int kSlots = 2 * kLines;                                     // load instructions per 16-row block
+    static constexpr int D = kSlots >= 4 ? 8 : 4;                                 // 1 KiB load instructions in flight per wave
+    static constexpr int NB = D / kSlots;                                         // 16-row blocks per loop iteration
+    static constexpr int kMfmaPerLine = FMT == 0 ? 2 : FMT == VT_Q_FP8_E4M3 ? 4 : 8;  // a line holds 64 / 128 / 256 weights
+    static constexpr int kHFrags = kCols / 32;                                    // B fragments (32 columns each)
+    static constexpr int kHLines = kCols * 2 / 128;                               // 128-byte lines of a hidden state's share
+    static constexpr int kHPieces = H / 8;                                        // 16-byte pieces per hidden state
+    static_assert(kLines >= 1 && kRowBytes == kLines * 128 * 16, "a wave reads whole 128-byte lines of a row");
+    static_assert(kHFrags == kLines * kMfmaPerLine && kHFrags == 2 * kHLines, "fragment counts agree");
+    static_assert(NB >= 1 && NB <= 2, "partial-sum planes for at most two blocks");
+};
+
+// Two E4M3 words (eight codes) -> an A fragment of eight bf16 (exact).
+__device__ __forceinline__ bf16x8 few_cvt_fp8(uint32_t lo, uint32_t hi)
+{
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    const b2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, false);
+    const b2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, 1.0f, true);
+    const b2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, false);
+    const b2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, 1.0f, true);
+    return bf16x8{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+}
+// One word of eight E2M1 codes (even element in the low nibble) times a power of two -> eight bf16 (exact).
+__device__ __forceinline__ bf16x8 few_cvt_fp4(uint32_t w, float scale)
+{
+    typedef __bf16 b2 __attribute__((ext_vector_type(2)));
+    const b2 p0 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, scale, 0);
+    const b2 p1 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, scale, 1);
+    const b2 p2 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, scale, 2);
+    const b2 p3 = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp4(w, scale, 3);
+    return bf16x8{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+}
+
+// SHARED: several workgroups (one per group of 16 hidden states) stream the same W_sub rows side by
+// side, so the loads leave the lines in the cache for the neighbours instead of marking them as used once.
+template <int FMT, int H, bool SHARED>
 __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
 {
-    constexpr int D = kFewSlots;
-    constexpr int NB = D / KS;          // 16-row blocks per loop iteration
-    constexpr int nchunk = 64 * KS;     // 16-byte pieces per W_sub row
-    static_assert(KS == 4 || KS == 8, "whole 128-byte lines per wave and row, whole blocks per iteration");
+    using G = FewGeom<FMT, H>;
+    constexpr int D = G::D;
+    constexpr int NB = G::NB;
+    constexpr int KSL = G::kSlots;
+    constexpr int NHF = G::kHFrags;
     extern __shared__ u32x4 smem[];
     __shared__ int s_flag;
 
@@ -96,30 +137,47 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
 
     // B operands: the wave's columns of every hidden state, requested before anything else (hidden
     // states beyond `rows` repeat state 0 and are zeroed once they are fragments)
-    u32x4 hreg[KS];
+    u32x4 hreg[NHF];
 #pragma unroll
-    for (int d = 0; d < KS; ++d) {
+    for (int d = 0; d < NHF; ++d) {
         const int r = ld_row + ((d & 1) ? 8 : 0);
-        hreg[d] = a.h[(size_t)(s0 + (r < rows ? r : 0)) * nchunk + wave * (KS * 4) + (d >> 1) * 8 + ((d & 1) ? pc_b : pc_a)];
+        hreg[d] = a.h[(size_t)(s0 + (r < rows ? r : 0)) * G::kHPieces + wave * (G::kHLines * 8) + (d >> 1) * 8 +
+                      ((d & 1) ? pc_b : pc_a)];
     }
 
-    // A operands.  Slot d of an iteration: block d / KS, 128-byte line (d % KS) / 2 of the wave's
-    // columns, rows 0..7 (even d) or 8..15 (odd d) of the block.  Rows past the workgroup's run
-    // repeat its last row (their results are dropped).
-    const u32x4* wbase = a.W + (size_t)j0 * nchunk + wave * (KS * 4);
+    // A operands.  Slot d of an iteration: block d / KSL, 128-byte line (d % KSL) / 2 of the wave's
+    // share of the row, rows 0..7 (even d) or 8..15 (odd d) of the block.  Rows past the workgroup's
+    // run repeat its last row (their results are dropped).
+    const u32x4* wbase = a.W + (size_t)j0 * G::kPieces + wave * (G::kLines * 8);
     u32x4 buf[D];
     auto issue = [&](int it, int d) {
-        const int blk = it * NB + d / KS;
+        const int blk = it * NB + d / KSL;
         int r = blk * 16 + ld_row + ((d & 1) ? 8 : 0);
         r = r < n_wg ? r : n_wg - 1;
-        const int piece = ((d % KS) >> 1) * 8 + ((d & 1) ? pc_b : pc_a);
+        const int piece = ((d % KSL) >> 1) * 8 + ((d & 1) ? pc_b : pc_a);
         if constexpr (SHARED)
-            buf[d] = wbase[(size_t)r * nchunk + piece];
+            buf[d] = wbase[(size_t)r * G::kPieces + piece];
         else
-            buf[d] = __builtin_nontemporal_load(wbase + (size_t)r * nchunk + piece);
+            buf[d] = __builtin_nontemporal_load(wbase + (size_t)r * G::kPieces + piece);
+    };
+    // Scales.  FP8: the fp32 scale of block row c for lane c, fetched at the start of an iteration for
+    // its blocks (used after the block's sums are complete).  MXFP4: the eight exponent bytes of the
+    // wave's share of row l % 16 (one 8-byte load; byte g belongs to piece g, byte 4 + g to piece 4 + g),
+    // fetched with the block's pieces, one iteration ahead.
+    float rsc[NB];
+    u32x2 ebuf[NB];
+    auto issue_exp = [&](int it, int bi) {
+        int r = (it * NB + bi) * 16 + m16;
+        r = r < n_wg ? r : n_wg - 1;
+        ebuf[bi] = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint8_t*>(a.scales) +
+                                                  (size_t)(j0 + r) * (H / 32) + wave * (G::kCols / 32));
     };
 #pragma unroll
     for (int d = 0; d < D; ++d) {
+        if constexpr (FMT == VT_Q_MXFP4) {
+            if (d % KSL == 0)
+                issue_exp(0, d / KSL);
+        }
         issue(0, d);
         __builtin_amdgcn_sched_barrier(0);  // in slot order, as every later iteration requests them
     }
@@ -127,18 +185,45 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     u32x4* stage = reinterpret_cast<u32x4*>(lds + kFewLdsStage + wave * kFewStageBytes);
     float* part = reinterpret_cast<float*>(lds + kFewLdsPart);
     const int a_sw = (m16 >> 1) & 7;
-    // the hidden states become fragments while the first W_sub pieces are on their way
+    // The hidden states become fragments while the first W_sub pieces are on their way.  Which eight
+    // columns lane (state, g) needs for a fragment follows from where the format puts the weights of
+    // the piece the lane will read: bf16 pieces g and 4 + g of a line hold columns 8 g.. and 32 + 8 g..
+    // of its 64; an FP8 piece holds 16 columns, multiplied as two fragments, so hidden-state pieces
+    // 2 g and 2 g + 1; an MXFP4 piece holds 32 columns, four fragments, so pieces 4 (g % 2) + j of
+    // hidden-state line g / 2 (of the pair of lines staged together).
+    if constexpr (FMT == VT_Q_MXFP4) {
 #pragma unroll
-    for (int c = 0; c < KS / 2; ++c) {
-        u32x4* st = stage + (c & 1) * 128;
-        st[lane] = hreg[2 * c];
-        st[kWave + lane] = hreg[2 * c + 1];
-        __builtin_amdgcn_wave_barrier();
-        const u32x4 x0 = st[m16 * 8 + (g4 ^ a_sw)];
-        const u32x4 x1 = st[m16 * 8 + ((4 + g4) ^ a_sw)];
-        __builtin_amdgcn_wave_barrier();
-        hreg[2 * c] = m16 < rows ? x0 : u32x4{0u, 0u, 0u, 0u};
-        hreg[2 * c + 1] = m16 < rows ? x1 : u32x4{0u, 0u, 0u, 0u};
+        for (int t = 0; t < G::kHLines / 2; ++t) {
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                stage[e * 128 + lane] = hreg[4 * t + 2 * e];
+                stage[e * 128 + kWave + lane] = hreg[4 * t + 2 * e + 1];
+            }
+            __builtin_amdgcn_wave_barrier();
+            u32x4 x[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                x[j] = stage[(g4 >> 1) * 128 + m16 * 8 + ((4 * (g4 & 1) + j) ^ a_sw)];
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                hreg[4 * t + j] = m16 < rows ? x[j] : u32x4{0u, 0u, 0u, 0u};
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < G::kHLines; ++c) {
+            u32x4* st = stage + (c & 1) * 128;
+            st[lane] = hreg[2 * c];
+            st[kWave + lane] = hreg[2 * c + 1];
+            __builtin_amdgcn_wave_barrier();
+            const int p0 = FMT == 0 ? g4 : 2 * g4;
+            const int p1 = FMT == 0 ? 4 + g4 : 2 * g4 + 1;
+            const u32x4 x0 = st[m16 * 8 + (p0 ^ a_sw)];
+            const u32x4 x1 = st[m16 * 8 + (p1 ^ a_sw)];
+            __builtin_amdgcn_wave_barrier();
+            hreg[2 * c] = m16 < rows ? x0 : u32x4{0u, 0u, 0u, 0u};
+            hreg[2 * c + 1] = m16 < rows ? x1 : u32x4{0u, 0u, 0u, 0u};
+        }
     }
 
     // wave r < rows keeps the results of hidden state s0 + r: the running list of its 16 best (lane q of every
@@ -160,14 +245,32 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
         return part + ((buf_i * NB + bi) * kGemvWaves + p) * (kFewPlaneBytes / 4) + l * 4 + (l >> 4) * 4;
     };
 
+    auto mfma = [&](const bf16x8& av, int hf, int bi) {
+        acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av, __builtin_bit_cast(bf16x8, hreg[hf]), acc[bi], 0, 0, 0);
+    };
     auto iteration = [&](int it, auto more_c) {
         constexpr bool MORE = decltype(more_c)::value;  // another iteration follows: its loads are unconditional
+        if constexpr (FMT == VT_Q_FP8_E4M3) {
+#pragma unroll
+            for (int bi = 0; bi < NB; ++bi) {
+                int r = (it * NB + bi) * 16 + m16;
+                r = r < n_wg ? r : n_wg - 1;
+                rsc[bi] = reinterpret_cast<const float*>(a.scales)[j0 + r];
+            }
+        }
 #pragma unroll
         for (int c = 0; c < D / 2; ++c) {
             u32x4* st = stage + (c & 1) * 128;
             st[lane] = buf[2 * c];
             st[kWave + lane] = buf[2 * c + 1];
+            const int bi = (2 * c) / KSL;          // block of the iteration
+            const int ln = ((2 * c) % KSL) >> 1;   // line of the wave's share of its rows
+            u32x2 eb = {0u, 0u};
+            if constexpr (FMT == VT_Q_MXFP4)
+                eb = ebuf[bi];
             if (MORE) {
+                if constexpr (FMT == VT_Q_MXFP4)
+                    issue_exp(it + 1, bi);
                 issue(it + 1, 2 * c);
                 issue(it + 1, 2 * c + 1);
             }
@@ -175,12 +278,25 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
             const u32x4 w0 = st[m16 * 8 + (g4 ^ a_sw)];
             const u32x4 w1 = st[m16 * 8 + ((4 + g4) ^ a_sw)];
             __builtin_amdgcn_wave_barrier();
-            const int bi = (2 * c) / KS;
-            const int i0 = (2 * c) % KS;
-            acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w0),
-                                                             __builtin_bit_cast(bf16x8, hreg[i0]), acc[bi], 0, 0, 0);
-            acc[bi] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w1),
-                                                             __builtin_bit_cast(bf16x8, hreg[i0 + 1]), acc[bi], 0, 0, 0);
+            if constexpr (FMT == 0) {
+                mfma(__builtin_bit_cast(bf16x8, w0), 2 * ln, bi);
+                mfma(__builtin_bit_cast(bf16x8, w1), 2 * ln + 1, bi);
+            } else if constexpr (FMT == VT_Q_FP8_E4M3) {
+                mfma(few_cvt_fp8(w0[0], w0[1]), 4 * ln, bi);
+                mfma(few_cvt_fp8(w0[2], w0[3]), 4 * ln + 1, bi);
+                mfma(few_cvt_fp8(w1[0], w1[1]), 4 * ln + 2, bi);
+                mfma(few_cvt_fp8(w1[2], w1[3]), 4 * ln + 3, bi);
+            } else {
+                // the piece's block exponent becomes the conversion's scale: 2^(byte - 127) as an fp32
+                const float sc0 = __uint_as_float(((eb[0] >> (8 * g4)) & 0xffu) << 23);
+                const float sc1 = __uint_as_float(((eb[1] >> (8 * g4)) & 0xffu) << 23);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    mfma(few_cvt_fp4(w0[j], sc0), j, bi);
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    mfma(few_cvt_fp4(w1[j], sc1), 4 + j, bi);
+            }
         }
         // the wave's partial sums of the iteration's blocks go to plane it % 2: lane (state m16, g4)
         // holds block rows 4 g4 .. 4 g4 + 3 of that state
@@ -205,6 +321,8 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
             float z = (x0 + x1) + (x2 + x3);
             z += xchg_f<16>(z, lane);
             z += xchg_f<32>(z, lane);
+            if constexpr (FMT == VT_Q_FP8_E4M3)
+                z *= rsc[bi];  // the row's scale multiplies the row's sum
             const int jb = (it * NB + bi) * 16;  // the block's first row within the workgroup's run
             const bool valid = jb + m16 < n_wg;
             const int zk = valid ? f2key(z) : kKeyNone;
@@ -361,33 +479,50 @@ static bool few_rows_launch_ok(const Plan& p, const GemvArgs& ga)
         return false;
     const int nb = p.blocks / nsg;
     return p.blocks == nb * nsg && nb >= 1 && nb <= 16 * (16 / nsg) && ga.KP == 16 && ga.k <= 16 && ga.P == nb + 16 &&
-           ga.fused && (p.H == 2048 || p.H == 4096) && ga.nchunk == p.H / 8;
+           ga.fused && (p.H == 2048 || p.H == 4096);
 }
 
-template <int KS, bool SHARED>
+template <int FMT, int H, bool SHARED>
 static hipError_t launch_few_t(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
-    constexpr int lds = few_lds_bytes(kFewSlots / KS);
+    constexpr int lds = few_lds_bytes(FewGeom<FMT, H>::NB);
     static_assert(lds <= kGemvLdsLimit, "fits a compute unit's LDS");
     static std::atomic<int> raised{0};  // the dynamic LDS limit of this instantiation is raised once
     if (!raised.load()) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_few_rows_kernel<KS, SHARED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(gemv_few_rows_kernel<FMT, H, SHARED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, lds);
         if (e != hipSuccess)
             return e;
         raised.store(1);
     }
-    hipLaunchKernelGGL((gemv_few_rows_kernel<KS, SHARED>), dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
+    hipLaunchKernelGGL((gemv_few_rows_kernel<FMT, H, SHARED>), dim3(p.blocks), dim3(kGemvThreads), lds, s, ga);
     return hipGetLastError();
+}
+
+template <int FMT, int H>
+static hipError_t launch_few_fh(const Plan& p, const GemvArgs& ga, hipStream_t s)
+{
+    return ga.nsg > 1 ? launch_few_t<FMT, H, true>(p, ga, s) : launch_few_t<FMT, H, false>(p, ga, s);
 }
 
 hipError_t launch_gemv_few_rows(const Plan& p, const GemvArgs& ga, hipStream_t s)
 {
-    if (!few_rows_launch_ok(p, ga))
+    if (!few_rows_launch_ok(p, ga) || ga.nchunk != p.H / 8)
         return hipErrorInvalidValue;
-    if (ga.nsg > 1)
-        return p.H == 4096 ? launch_few_t<8, true>(p, ga, s) : launch_few_t<4, true>(p, ga, s);
-    return p.H == 4096 ? launch_few_t<8, false>(p, ga, s) : launch_few_t<4, false>(p, ga, s);
+    return p.H == 4096 ? launch_few_fh<0, 4096>(p, ga, s) : launch_few_fh<0, 2048>(p, ga, s);
+}
+
+// The same over a compressed W_sub: FP8 at H = 2048 / 4096, MXFP4 at H = 4096 (a wave's share of a row is
+// then at least one 128-byte line).
+hipError_t launch_gemv_few_rows_q(int fmt, const Plan& p, const GemvArgs& ga, hipStream_t s)
+{
+    if (!few_rows_launch_ok(p, ga) || ga.scales == nullptr)
+        return hipErrorInvalidValue;
+    if (fmt == VT_Q_FP8_E4M3)
+        return p.H == 4096 ? launch_few_fh<VT_Q_FP8_E4M3, 4096>(p, ga, s) : launch_few_fh<VT_Q_FP8_E4M3, 2048>(p, ga, s);
+    if (fmt == VT_Q_MXFP4 && p.H == 4096)
+        return launch_few_fh<VT_Q_MXFP4, 4096>(p, ga, s);
+    return hipErrorInvalidValue;
 }
 
 }  // namespace vt

@@ -473,6 +473,8 @@ hipError_t launch_gemv_q(int fmt, const Plan& p, const HeadArgs& a, hipStream_t 
     GemvArgs ga;
     fill_gemv_args(p, a, ga);
     ga.nchunk = 0;  // the compressed kernels take the row length from the plan's hidden size
+    if (p.few_rows)
+        return launch_gemv_few_rows_q(fmt, p, ga, s);
     return launch_gemv_one_row_q(fmt, p, ga, s);
 }
 

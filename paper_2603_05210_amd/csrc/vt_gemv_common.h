@@ -49,6 +49,7 @@ __device__ __forceinline__ int ld_dev(const int* p) { return __hip_atomic_load(p
 
 hipError_t launch_gemv_one_row(const Plan& p, const GemvArgs& ga, hipStream_t s);
 hipError_t launch_gemv_few_rows(const Plan& p, const GemvArgs& ga, hipStream_t s);
+hipError_t launch_gemv_few_rows_q(int fmt, const Plan& p, const GemvArgs& ga, hipStream_t s);
 hipError_t launch_gemv_one_row_q(int fmt, const Plan& p, const GemvArgs& ga, hipStream_t s);
 hipError_t launch_gemv_q(int fmt, const Plan& p, const HeadArgs& a, hipStream_t s);
 

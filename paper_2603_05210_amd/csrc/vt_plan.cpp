@@ -155,13 +155,23 @@ bool make_plan(int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
 
 bool make_plan_q(int fmt, int64_t rows, int64_t H, int64_t Vd, int k, Plan& p)
 {
-    const bool h_ok = (fmt == VT_Q_FP8_E4M3 && (H == 1024 || H == 2048 || H == 4096)) ||
-                      (fmt == VT_Q_MXFP4 && (H == 2048 || H == 4096));
-    if (!h_ok || rows != 1 || k < 1 || k > 16 || Vd < 1 || Vd > (int64_t)kGemvTargetBlocks * kGemvWaves * 64)
+    if (k < 1 || k > 16 || Vd < 1)
         return false;
-    // the one-row plan of the bf16 head with the same V_draft and k (the hidden size only selects the kernel)
-    if (!make_plan(1, 4096, Vd, k, p) || !p.one_row)
-        return false;
+    if (rows == 1) {
+        const bool h_ok = (fmt == VT_Q_FP8_E4M3 && (H == 1024 || H == 2048 || H == 4096)) ||
+                          (fmt == VT_Q_MXFP4 && (H == 2048 || H == 4096));
+        if (!h_ok || Vd > (int64_t)kGemvTargetBlocks * kGemvWaves * 64)
+            return false;
+        // the one-row plan of the bf16 head with the same V_draft and k (the hidden size only selects the kernel)
+        if (!make_plan(1, 4096, Vd, k, p) || !p.one_row)
+            return false;
+    } else {
+        // a few rows: the plan of the bf16 kernel for a few rows (a wave's share of a compressed row must
+        // still be whole 128-byte lines: FP8 from H = 2048, MXFP4 at H = 4096)
+        const bool h_ok = (fmt == VT_Q_FP8_E4M3 && (H == 2048 || H == 4096)) || (fmt == VT_Q_MXFP4 && H == 4096);
+        if (!h_ok || !make_plan(rows, 4096, Vd, k, p) || !p.few_rows)
+            return false;
+    }
     p.H = (int)H;
     return true;
 }

@@ -38,8 +38,9 @@ def build_both(W_u16, ids, fmt, W_dev=None):
 
 def run_gpu(h_u16, codes, scales, fmt, d2t, k):
     Vd = codes.shape[0]
-    logits = torch.full((1, Vd), float("nan"), dtype=torch.float32, device=DEV)
-    lse = torch.full((1,), float("nan"), dtype=torch.float32, device=DEV)
+    R = h_u16.shape[0]
+    logits = torch.full((R, Vd), float("nan"), dtype=torch.float32, device=DEV)
+    lse = torch.full((R,), float("nan"), dtype=torch.float32, device=DEV)
     ids, lp = vt.vt_draft_head_q(to_dev_bf16(h_u16), codes, scales, fmt, d2t, k, logits_out=logits, lse_out=lse)
     torch.cuda.synchronize()
     ids2, lp2 = vt.vt_draft_head_q(to_dev_bf16(h_u16), codes, scales, fmt, d2t, k)   # the timed entry gives the same
@@ -102,10 +103,16 @@ def test_compressed_head_argument_errors():
     F = 0x1000
     wsb = vt.vt_draft_head_q_workspace_bytes(1, 1, 4096, 4096, 10)
     assert wsb > 0
-    assert vt.vt_draft_head_q_workspace_bytes(1, 2, 4096, 4096, 10) == 0       # one row only
+    assert vt.vt_draft_head_q_workspace_bytes(1, 2, 4096, 4096, 10) > 0        # a few rows: FP8 at H = 2048 / 4096 ...
+    assert vt.vt_draft_head_q_workspace_bytes(2, 8, 4096, 4096, 10) > 0        # ... MXFP4 at H = 4096
+    assert vt.vt_draft_head_q_workspace_bytes(1, 2, 1024, 4096, 10) == 0
+    assert vt.vt_draft_head_q_workspace_bytes(2, 2, 2048, 4096, 10) == 0
+    assert vt.vt_draft_head_q_workspace_bytes(1, 65, 4096, 4096, 10) == 0      # more rows than the streaming kernels take
+    assert vt.vt_draft_head_q_workspace_bytes(1, 48, 4096, 40000, 10) == 0     # three groups of rows only over narrow vocabularies
     assert vt.vt_draft_head_q_workspace_bytes(2, 1, 1024, 4096, 10) == 0       # MXFP4: H 2048 or 4096
     assert vt.vt_draft_head_q_workspace_bytes(3, 1, 4096, 4096, 10) == 0       # unknown format
-    assert L.vt_draft_head_q(F, 2, 4096, F, F, 1, F, 4096, 10, F, F, F, wsb, None) == 2
+    assert L.vt_draft_head_q(F, 2, 1024, F, F, 1, F, 4096, 10, F, F, F, wsb, None) == 2
+    assert L.vt_draft_head_q(F, 70, 4096, F, F, 1, F, 4096, 10, F, F, F, 1 << 24, None) == 2
     assert L.vt_draft_head_q(F, 1, 4096, F, F, 1, F, 4096, 17, F, F, F, wsb, None) == 3
     assert L.vt_draft_head_q(F, 1, 4096, F, F, 1, F, 4096, 10, F, F, F, wsb - 1, None) == 6
     assert L.vt_draft_head_q(None, 1, 4096, F, F, 1, F, 4096, 10, F, F, F, wsb, None) == 1
@@ -115,6 +122,56 @@ def test_compressed_head_argument_errors():
     assert L.vt_subset_q_code_bytes(1, 1000, 4096) == 1000 * 4096 and L.vt_subset_q_scale_bytes(1, 1000, 4096) == 4000
     assert L.vt_subset_q_code_bytes(2, 1000, 4096) == 1000 * 2048 and L.vt_subset_q_scale_bytes(2, 1000, 4096) == 1000 * 128
     assert L.vt_subset_q_code_bytes(2, 1000, 4112) == 0
+
+
+FEW = [
+    # fmt, rows, H, V, Vd, k
+    (vq.FMT_FP8, 2, 4096, 6000, 4099, 10),
+    (vq.FMT_FP8, 8, 4096, 14000, 13264, 8),
+    (vq.FMT_FP8, 16, 2048, 5000, 4097, 16),
+    (vq.FMT_FP8, 5, 2048, 300, 17, 5),          # two workgroups of 9 and 8 rows
+    (vq.FMT_FP8, 24, 4096, 3000, 2049, 10),     # two groups of rows
+    (vq.FMT_FP8, 40, 2048, 9000, 4380, 3),      # three groups
+    (vq.FMT_MXFP4, 2, 4096, 6000, 4099, 10),
+    (vq.FMT_MXFP4, 8, 4096, 14000, 13264, 8),
+    (vq.FMT_MXFP4, 13, 4096, 500, 16, 16),      # one workgroup, k == V_draft
+    (vq.FMT_MXFP4, 16, 4096, 9000, 8200, 16),   # ragged third block
+    (vq.FMT_MXFP4, 33, 4096, 3000, 257, 1),     # three groups, 17 runs: plain block numbering
+]
+
+
+@pytest.mark.parametrize("fmt,rows,H,V,Vd,k", FEW)
+def test_compressed_head_few_rows(fmt, rows, H, V, Vd, k):
+    """The step over a compressed W_sub for 2..64 hidden states (the kernel for a few rows with the codes
+    widened to bf16 fragments in registers): every logit, lse, id and log-probability against the oracle."""
+    _say("q few rows fmt=%d rows=%d H=%d V=%d Vd=%d k=%d" % (fmt, rows, H, V, Vd, k))
+    seed = rows * 31 + H + Vd + k
+    W = synth.gen_W(seed, V, H, std=0.05)
+    W[V // 2] = 0
+    W[V // 3, 32:96] = 0
+    h = synth.gen_h(seed, rows, H, peaked_frac=0.1 if rows >= 10 else 0.0)
+    ids = synth.zipf_subset(seed, V, Vd)
+    codes, scales, d2t, o_codes, o_scales, o_d2t = build_both(W, ids, fmt)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, codes, scales, fmt, d2t, k)
+    ora = vq.draft_head_q(h, o_codes, o_scales, fmt, o_d2t, k)
+    _say("  %s" % check_head(g_ids, g_lp, ora, o_d2t, gpu_logits=g_z, gpu_lse=g_lse))
+
+
+@pytest.mark.parametrize("rows", [2, 7, 16, 20])
+def test_mxfp4_few_rows_exact_arithmetic(rows):
+    """Small-integer weights survive MXFP4 unchanged (block maximum 2: exponent -1, codes 0, 2, 4), so with
+    small-integer hidden states every logit is an exact integer: bit for bit, ties by draft index."""
+    H, Vd, k = 4096, 3001, 12
+    Wb = synth.small_int_bf16(8, 0, (Vd, H), lo=-2, hi=2)
+    hb = synth.small_int_bf16(8, 1, (rows, H), lo=-2, hi=2)
+    ids = np.arange(Vd, dtype=np.int32)
+    codes, scales, d2t, o_codes, o_scales, o_d2t = build_both(Wb, ids, vq.FMT_MXFP4)
+    assert np.array_equal(vq.dequantize(o_codes, o_scales, vq.FMT_MXFP4), synth.bf16_to_f32(Wb))
+    g_ids, g_lp, g_z, _ = run_gpu(hb, codes, scales, vq.FMT_MXFP4, d2t, k)
+    ora = vq.draft_head_q(hb, o_codes, o_scales, vq.FMT_MXFP4, o_d2t, k)
+    assert np.array_equal(g_z.view(np.uint32), ora.z.view(np.uint32))
+    assert np.array_equal(g_ids, ora.ids)
+    assert np.max(np.abs(g_lp - ora.logp)) < 1e-3
 
 
 # ------------------------------------------------------------------ full-size workloads
