@@ -20,6 +20,11 @@
 //     beats the list's k-th entry -- rare once the list has warmed up -- by one shifted copy and
 //     two compares.  Which wave and lane see which W_sub row is fixed by the row's number, so the
 //     result does not depend on timing;
+//   - a compressed W_sub (FP8 E4M3 with a scale per row, MXFP4 with an exponent per 32 weights: the
+//     forms of vt_gemvq.hip) takes the same path: a staged 16-byte piece holds 16 or 32 codes, which
+//     the hardware conversions widen to two or four bf16 fragments in registers (exact; an MXFP4
+//     block's power of two goes in as the conversion's scale, an FP8 row's scale multiplies the
+//     row's finished sum), and the hidden states' fragments are cut to match;
 //   - lists travel as 64-bit order keys (logit key, then lower draft index) and are merged by the
 //     bitonic network, one wave per hidden state: the lists of each group of 16 workgroups by the
 //     last of the group to arrive, then the groups' lists by the last group to finish, which
