@@ -122,9 +122,33 @@ __global__ void __launch_bounds__(kCovLdsThreads) coverage_lds_kernel(const int3
         if ((s_seen[t >> 5] & bit) == 0u)
             atomicOr(&s_seen[t >> 5], bit);
     };
+    // 16-byte loads over the 16-byte aligned middle of the stream, four per thread in flight; the few
+    // tokens before and after it one by one
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    int64_t head = (int64_t)((16u - (unsigned int)(reinterpret_cast<uintptr_t>(tokens) & 15u)) & 15u) >> 2;
+    head = head < n ? head : n;
+    const i32x4* t4 = reinterpret_cast<const i32x4*>(tokens + head);
+    const int64_t n4 = (n - head) >> 2;
     const int64_t stride = (int64_t)gridDim.x * kCovLdsThreads;
-    for (int64_t i = (int64_t)blockIdx.x * kCovLdsThreads + threadIdx.x; i < n; i += stride)
-        take(__builtin_nontemporal_load(tokens + i));
+    for (int64_t j = (int64_t)blockIdx.x * kCovLdsThreads + threadIdx.x; j < head; j += stride)
+        take(tokens[j]);
+    int64_t i = (int64_t)blockIdx.x * kCovLdsThreads + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const i32x4 q0 = __builtin_nontemporal_load(t4 + i);
+        const i32x4 q1 = __builtin_nontemporal_load(t4 + i + stride);
+        const i32x4 q2 = __builtin_nontemporal_load(t4 + i + 2 * stride);
+        const i32x4 q3 = __builtin_nontemporal_load(t4 + i + 3 * stride);
+        take(q0.x), take(q0.y), take(q0.z), take(q0.w);
+        take(q1.x), take(q1.y), take(q1.z), take(q1.w);
+        take(q2.x), take(q2.y), take(q2.z), take(q2.w);
+        take(q3.x), take(q3.y), take(q3.z), take(q3.w);
+    }
+    for (; i < n4; i += stride) {
+        const i32x4 q = __builtin_nontemporal_load(t4 + i);
+        take(q.x), take(q.y), take(q.z), take(q.w);
+    }
+    for (int64_t j = head + (n4 << 2) + (int64_t)blockIdx.x * kCovLdsThreads + threadIdx.x; j < n; j += stride)
+        take(tokens[j]);
     for (int off = 32; off > 0; off >>= 1)
         covered += __shfl_xor(covered, off, 64);
     if ((threadIdx.x & 63) == 0 && covered != 0)

@@ -54,6 +54,22 @@ def test_coverage_matches_oracle(V, Vd, n, support):
         assert res.freq_coverage == 1.0 and res.unique_coverage == 1.0
 
 
+@pytest.mark.parametrize("skip", [1, 2, 3])
+def test_long_stream_that_starts_off_a_16_byte_boundary(skip):
+    """The ratios-only call reads the stream with 16-byte loads over its aligned middle: a stream that
+    starts 4, 8 or 12 bytes past a boundary (and ends raggedly) gives the oracle's counts all the same."""
+    V, Vd, n = 128256, 6521, 1_200_003
+    tokens = synth.zipf_token_stream(11, V, n + skip)
+    d2t = synth.zipf_subset(11, V, Vd)
+    t2d_dev = vt.vt_build_t2d(_dev(d2t), V)
+    view = _dev(tokens)[skip:]
+    assert view.data_ptr() % 16 == 4 * skip
+    res, none = vt.vt_coverage(view, t2d_dev)
+    ora = vc.coverage(tokens[skip:], vc.build_t2d(d2t, V))
+    got = (int(res.n_tokens), int(res.n_covered), int(res.n_unique), int(res.n_unique_covered))
+    assert got == (ora.n_tokens, ora.n_covered, ora.n_unique, ora.n_unique_covered), (got, ora)
+
+
 def test_unsorted_draft_order_is_kept():
     V = 300
     d2t = synth.zipf_subset(1, V, 40)[::-1].copy()
