@@ -487,6 +487,21 @@ def test_cfg2_vocab_sweep(W4096, Vd):
     _say("cfg2 Vd=%d %s" % (Vd, check_head(g_ids, g_lp, ora, ids, gpu_logits=g_z, gpu_lse=g_lse)))
 
 
+@pytest.mark.parametrize("rows,Vd,k", [(8, 13264, 8), (32, 13264, 8), (16, synth.FULL_VOCAB, 10), (32, synth.FULL_VOCAB, 10)])
+def test_tree_step_of_a_few_rows_full_size(W4096, rows, Vd, k):
+    """The tree-drafting steps bench.py times (8 and 32 nodes over the vocabulary Section 2.6 selects) and
+    the kernel for a few rows over the whole vocabulary, one and two groups of rows: every logit, lse, id
+    and log-probability against the oracle."""
+    ids, Wsub_dev, d2t_dev = _subset(W4096, Vd)
+    h = synth.gen_h(0, rows, 4096)
+    assert vt.vt_draft_head_regime(rows, 4096, Vd, k) == 0
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, Wsub_dev, d2t_dev, k)
+    ora = vo.draft_head(h, W4096[0] if Vd == synth.FULL_VOCAB else W4096[0][ids], ids, k)
+    _say("tree step rows=%d Vd=%d %s" % (rows, Vd, check_head(g_ids, g_lp, ora, ids, gpu_logits=g_z, gpu_lse=g_lse)))
+    n_ids, n_lp, _, _ = run_gpu(h, Wsub_dev, d2t_dev, k, debug=False)   # the timed entry point
+    assert np.array_equal(n_ids, g_ids) and np.array_equal(n_lp, g_lp)
+
+
 def _all_rows_check(name, W_pair, Vd, rows, k, peaked, chunk=64, logits_block=(0, 256)):
     """Every row of a tree-drafting-size batch against the oracle: ids (near-tie rule) and
     log-probs from the launch configuration that is timed (all rows in one call, no logits

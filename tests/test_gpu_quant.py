@@ -194,3 +194,17 @@ def test_compressed_vocab_sweep_full_size(W4096, fmt, Vd):
     g_ids, g_lp, g_z, g_lse = run_gpu(h, codes, scales, fmt, d2t, 10)
     ora = vq.draft_head_q(h, o_codes, o_scales, fmt, o_d2t, 10)
     _say("q fmt=%d Vd=%d %s" % (fmt, Vd, check_head(g_ids, g_lp, ora, o_d2t, gpu_logits=g_z, gpu_lse=g_lse)))
+
+
+@pytest.mark.parametrize("fmt", FMTS)
+@pytest.mark.parametrize("rows,Vd", [(8, 13264), (16, 128256)])
+def test_compressed_tree_step_full_size(W4096, fmt, rows, Vd):
+    """A tree-drafting step over the compressed forms at the sizes bench.py times and over the whole
+    vocabulary: every logit, lse, id and log-probability against the oracle."""
+    W, W_dev = W4096
+    ids = synth.zipf_subset(0, synth.FULL_VOCAB, Vd)
+    codes, scales, d2t, o_codes, o_scales, o_d2t = build_both(W, ids, fmt, W_dev=W_dev)
+    h = synth.gen_h(0, rows, 4096)
+    g_ids, g_lp, g_z, g_lse = run_gpu(h, codes, scales, fmt, d2t, 8)
+    ora = vq.draft_head_q(h, o_codes, o_scales, fmt, o_d2t, 8)
+    _say("q tree step fmt=%d rows=%d Vd=%d %s" % (fmt, rows, Vd, check_head(g_ids, g_lp, ora, o_d2t, gpu_logits=g_z, gpu_lse=g_lse)))
