@@ -182,6 +182,20 @@ def test_flop_count_is_2dk_per_row(golden_dir):
 
 
 # ---------------------------------------------------------------- P6 zero hidden state
+def test_rows_of_a_batch_are_independent():
+    """The head is defined row by row: a batch (the nodes of a tree-drafting step) gives what its rows give
+    alone, whatever their order, bit for bit."""
+    V, H, k = 700, 96, 9
+    W = synth.gen_W(13, V, H, std=0.05)
+    h = synth.gen_h(13, 11, H, peaked_frac=0.2)
+    d2t = np.arange(V, dtype=np.int32)[::-1].copy()
+    res = vo.draft_head(h, W, d2t, k)
+    perm = [7, 0, 10, 3]
+    sub = vo.draft_head(h[perm], W, d2t, k)
+    assert np.array_equal(sub.ids, res.ids[perm]) and np.array_equal(sub.logp.view(np.uint32), res.logp[perm].view(np.uint32))
+    assert np.array_equal(sub.z.view(np.uint32), res.z[perm].view(np.uint32)) and np.array_equal(sub.lse, res.lse[perm])
+
+
 def test_zero_hidden_state_gives_uniform_distribution():
     W, _, ids = _small_problem(seed=6, V=400, H=64, Vd=123)
     W_sub, d2t = vo.build_subset(W, ids)

@@ -155,6 +155,11 @@ def test_compressed_head_invariants(fmt):
     for r in range(3):
         order = sorted(range(Vd), key=lambda j: (-res.z[r, j], j))[:k]
         assert list(res.draft_idx[r]) == order and list(res.ids[r]) == [int(d2t[j]) for j in order]
+    # rows are independent: a batch gives what its rows give one at a time, in any order, bit for bit
+    for r in (2, 0):
+        one = vq.draft_head_q(h[r:r + 1], codes, scales, fmt, d2t, k)
+        assert np.array_equal(one.z.view(np.uint32), res.z[r:r + 1].view(np.uint32)) and np.array_equal(one.ids, res.ids[r:r + 1])
+        assert np.array_equal(one.logp.view(np.uint32), res.logp[r:r + 1].view(np.uint32))
     # zero hidden state: uniform distribution, first k draft tokens
     z0 = vq.draft_head_q(np.zeros((1, H), dtype=np.uint16), codes, scales, fmt, d2t, k)
     assert np.allclose(z0.logp, -np.log(Vd), atol=1e-6) and list(z0.ids[0]) == list(d2t[:k])
