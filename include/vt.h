@@ -123,7 +123,9 @@ int vt_draft_head_regime(int64_t rows, int64_t H, int64_t V_draft, int k);
  * Asynchronous on `stream`: no allocation, no synchronisation, no host read.  Calls that may
  * overlap in time (different streams) must not share a workspace: it holds the call's partial
  * results and the arrival counter of its single-launch merge.  Calls on one stream run in order
- * and may share one.  The logits are never written to memory.
+ * and may share one.  The logits are never written to memory.  The first call of a kernel family
+ * in a process may raise that kernel's dynamic shared-memory limit (a driver call, not a stream
+ * operation): before capturing a call into a HIP graph, run it once outside the capture.
  */
 vt_status vt_draft_head(const uint16_t *h, int64_t rows, int64_t H, const uint16_t *W_sub,
                         const int32_t *d2t, int64_t V_draft, int k, int32_t *out_target_ids,
