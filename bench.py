@@ -194,7 +194,11 @@ class Runner:
         build_ms = e0.elapsed_time(e1)
         n_copies = max(2, -(-(1 << 30) // nbytes))
         copies = [first] + [tuple(t.clone() for t in first) for _ in range(n_copies - 1)]
-        ws = vt.new_workspace(vt.vt_draft_head_fused_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"]), self.dev)
+        if kind == "head_q":
+            need = vt.vt_draft_head_q_workspace_bytes(w["fmt"], w["rows"], w["H"], w["Vd"], w["k"])
+        else:   # the fused call's need covers the plain call's
+            need = vt.vt_draft_head_fused_workspace_bytes(w["rows"], w["H"], w["Vd"], w["k"])
+        ws = vt.new_workspace(need, self.dev)
         out_ids = torch.empty((w["rows"], w["k"]), dtype=torch.int32, device=self.dev)
         out_lp = torch.empty((w["rows"], w["k"]), dtype=torch.float32, device=self.dev)
         if self.operands == "zero_h":

@@ -474,13 +474,13 @@ __global__ void __launch_bounds__(kGemvThreads) gemv_few_rows_kernel(GemvArgs a)
     emit();
 }
 
-// What the kernel assumes of a launch: 2..64 hidden states in nsg groups of 16, lists of 16, per group
+// What the kernel assumes of a launch: 1..64 hidden states in nsg groups of 16, lists of 16, per group
 // of states at most 256 / nsg workgroups (16 / nsg groups of 16, so that the arrival counters fit the
 // workspace header), result slots for every workgroup and every group of workgroups.
 static bool few_rows_launch_ok(const Plan& p, const GemvArgs& ga)
 {
     const int nsg = ga.nsg;
-    if (!(p.few_rows && ga.rows >= 2 && nsg >= 1 && nsg <= 4 && nsg == (ga.rows + 15) / 16))
+    if (!(p.few_rows && ga.rows >= 1 && nsg >= 1 && nsg <= 4 && nsg == (ga.rows + 15) / 16))
         return false;
     const int nb = p.blocks / nsg;
     return p.blocks == nb * nsg && nb >= 1 && nb <= 16 * (16 / nsg) && ga.KP == 16 && ga.k <= 16 && ga.P == nb + 16 &&

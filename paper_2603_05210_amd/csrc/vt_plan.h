@@ -16,6 +16,7 @@ constexpr int kFewMaxRows = 64;  // the kernel for a few rows: up to four groups
 // three or four groups only over a narrow vocabulary (measured at H = 4096, 48 / 64 rows: 44 / 46 us
 // against the GEMM regime's 57 at V_draft = 13264, 88 / 94 against 85 at 32768)
 constexpr int kFewWideMaxVd = 16384;
+constexpr int kFewOneRowMinVd = 8192;  // one MXFP4 row goes to that kernel from this vocabulary size on
 constexpr int kGemvThreads = 1024;
 constexpr int kGemvWaves = kGemvThreads / 64;
 constexpr int kGemvMaxRowsPerBlock = 512;  // W_sub rows one workgroup may own (8 logits per lane at the end)
